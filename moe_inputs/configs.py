@@ -1,0 +1,64 @@
+"""The five layer shapes the hot path is exercised on.
+
+The paper names the models (Section 4.1, "Models") but not their layer
+dimensions; the dimensions, token counts, top-k and skew recipes here are the
+benchmark definition this build was given.  The paper's own runs use sequence
+length 4096 and token-drop training with capacity factor 1 (Section 4.1 and
+Appendix "Parallel mappings"), which is where T = 2 x 4096 and CF = 1.0 come
+from.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Optional
+
+
+@dataclass(frozen=True)
+class LayerConfig:
+    name: str
+    T: int                 # tokens on this GPU
+    H: int                 # model hidden size
+    E: int                 # routed experts
+    K: int                 # experts per token
+    F: int                 # routed-expert FFN (intermediate) size
+    dtype: str             # "f32" or "bf16": storage type of x and the weights
+    renormalize: bool      # divide the K selected gates by their sum
+    seed: int
+    capacity_factor: Optional[float] = None   # None = dropless
+    bias: Optional[str] = None                # None | "normal" | "zipf1.2"
+    shared_F: int = 0                         # FFN size of the always-on shared expert (0 = none)
+
+    def scaled(self, **kw) -> "LayerConfig":
+        """A smaller/larger copy with the same recipe (used by parity tests)."""
+        return replace(self, **kw)
+
+    @property
+    def assignments(self) -> int:
+        return self.T * self.K
+
+
+CONFIGS = {
+    # cfg 1: the small case the CPU oracle finishes in well under a second.
+    "tiny": LayerConfig("tiny", T=256, H=128, E=8, K=2, F=256, dtype="f32",
+                        renormalize=True, seed=1001),
+    # cfg 2
+    "mixtral8x7b": LayerConfig("mixtral8x7b", T=8192, H=4096, E=8, K=2, F=14336,
+                               dtype="bf16", renormalize=True, seed=1002),
+    # cfg 3: the shape the roofline targets are quoted on.
+    "mixtral8x22b": LayerConfig("mixtral8x22b", T=8192, H=6144, E=8, K=2, F=16384,
+                                dtype="bf16", renormalize=True, seed=1003, bias="normal"),
+    # cfg 4
+    "qwen2_57b_a14b": LayerConfig("qwen2_57b_a14b", T=8192, H=3584, E=64, K=8, F=2560,
+                                  dtype="bf16", renormalize=False, seed=1004, shared_F=20480),
+    # cfg 5
+    "tokendrop": LayerConfig("tokendrop", T=32768, H=4096, E=64, K=6, F=1408,
+                             dtype="bf16", renormalize=False, seed=1005,
+                             capacity_factor=1.0, bias="zipf1.2"),
+}
+
+
+def get_config(name: str) -> LayerConfig:
+    try:
+        return CONFIGS[name]
+    except KeyError:
+        raise KeyError(f"unknown config {name!r}; have {sorted(CONFIGS)}") from None

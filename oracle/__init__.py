@@ -1,0 +1,205 @@
+"""ctypes access to the CPU oracle (oracle/moe_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke()``
+and by ``bench.py``'s cpu_baseline leg, never by the product package.
+
+Arrays holding layer tensors are float32 (fp32 configs) or uint16 bf16 bit
+patterns (bf16 configs); the C side widens either exactly to double.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Optional, Tuple
+
+import numpy as np
+
+from .build import build as _build
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        L = C.CDLL(_build())
+        L.oracle_num_threads.restype = C.c_int
+        L.oracle_capacity.restype = C.c_int
+        L.oracle_capacity.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int]
+        L.oracle_permute.restype = C.c_int
+        L.oracle_layer_forward.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _dt(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return 0
+    if a.dtype == np.uint16:
+        return 1
+    raise TypeError(f"layer tensors must be float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _p(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"], "oracle needs C-contiguous arrays"
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def capacity(cf: float, T: int, K: int, E: int) -> int:
+    return int(lib().oracle_capacity(float(cf), T, K, E))
+
+
+def router_logits(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray]) -> np.ndarray:
+    T, H = x.shape
+    E = w_router.shape[0]
+    assert w_router.shape == (E, H) and _dt(x) == _dt(w_router)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        assert bias.shape == (E,)
+    out = np.empty((T, E), dtype=np.float64)
+    lib().oracle_router_logits(_p(x), _p(w_router), _p(bias), T, H, E, _dt(x), _p(out))
+    return out
+
+
+def topk_gates(logits32: np.ndarray, K: int, renormalize: bool,
+               want_probs: bool = False):
+    logits32 = np.ascontiguousarray(logits32)
+    assert logits32.dtype == np.float32
+    T, E = logits32.shape
+    assert 1 <= K <= E
+    idx = np.empty((T, K), dtype=np.int32)
+    gate = np.empty((T, K), dtype=np.float64)
+    probs = np.empty((T, E), dtype=np.float64) if want_probs else None
+    lib().oracle_topk_gates(_p(logits32), T, E, K, int(bool(renormalize)), _p(idx), _p(gate), _p(probs))
+    return (idx, gate, probs) if want_probs else (idx, gate)
+
+
+class Permutation:
+    """Result of oracle_permute."""
+    def __init__(self, R, x_perm, counts, offsets, row_of_assign, assign_of_row):
+        self.R = R
+        self.x_perm = x_perm
+        self.counts = counts
+        self.offsets = offsets
+        self.row_of_assign = row_of_assign
+        self.assign_of_row = assign_of_row
+
+
+def permute(x: Optional[np.ndarray], idx: np.ndarray, E: int, capacity_rows: int = 0,
+            r_max: Optional[int] = None, H: Optional[int] = None) -> Permutation:
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    T, K = idx.shape
+    if x is not None:
+        assert x.shape[0] == T
+        H = x.shape[1]
+        dt = _dt(x)
+    else:
+        H = H or 1
+        dt = 0
+    if r_max is None:
+        r_max = T * K if capacity_rows <= 0 else min(T * K, E * capacity_rows)
+    x_perm = None
+    if x is not None:
+        x_perm = np.zeros((r_max, H), dtype=x.dtype)
+    counts = np.empty(E, dtype=np.int32)
+    offsets = np.empty(E + 1, dtype=np.int32)
+    roa = np.empty(T * K, dtype=np.int32)
+    aor = np.empty(max(r_max, 1), dtype=np.int32)
+    R = lib().oracle_permute(_p(x), _p(idx), T, H, E, K, int(capacity_rows), dt, r_max,
+                             _p(x_perm), _p(counts), _p(offsets), _p(roa), _p(aor))
+    return Permutation(int(R), x_perm, counts, offsets, roa, aor[:r_max])
+
+
+def expert_ffn_rows(x_rows: np.ndarray, w_gate: np.ndarray, w_up: np.ndarray, w_down: np.ndarray,
+                    want_h: bool = False):
+    """One expert's SwiGLU FFN over the given rows; returns y (and h) in double."""
+    n, H = x_rows.shape
+    F = w_gate.shape[0]
+    assert w_gate.shape == (F, H) and w_up.shape == (F, H) and w_down.shape == (H, F)
+    dt = _dt(x_rows)
+    assert dt == _dt(w_gate) == _dt(w_up) == _dt(w_down)
+    x_rows = np.ascontiguousarray(x_rows)
+    y = np.zeros((n, H), dtype=np.float64)
+    h = np.zeros((n, F), dtype=np.float64) if want_h else None
+    lib().oracle_expert_ffn_rows(_p(x_rows), n, H, F, _p(w_gate), _p(w_up), _p(w_down), dt, _p(h), _p(y))
+    return (y, h) if want_h else y
+
+
+def experts(x_perm: np.ndarray, offsets: np.ndarray, w_gate: np.ndarray, w_up: np.ndarray,
+            w_down: np.ndarray, want_h: bool = False):
+    E, F, H = w_gate.shape
+    assert w_up.shape == (E, F, H) and w_down.shape == (E, H, F)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+    assert offsets.shape == (E + 1,)
+    R = int(offsets[E])
+    assert x_perm.shape[0] >= R and x_perm.shape[1] == H
+    dt = _dt(x_perm)
+    y = np.zeros((R, H), dtype=np.float64)
+    h = np.zeros((R, F), dtype=np.float64) if want_h else None
+    lib().oracle_experts(_p(x_perm), _p(offsets), E, H, F, _p(w_gate), _p(w_up), _p(w_down), dt, _p(h), _p(y))
+    return (y, h) if want_h else y
+
+
+def combine(y_perm: np.ndarray, row_of_assign: np.ndarray, gate: np.ndarray,
+            addend: Optional[np.ndarray] = None) -> np.ndarray:
+    y_perm = np.ascontiguousarray(y_perm, dtype=np.float64)
+    gate = np.ascontiguousarray(gate, dtype=np.float64)
+    T, K = gate.shape
+    H = y_perm.shape[1]
+    roa = np.ascontiguousarray(row_of_assign, dtype=np.int32).reshape(T * K)
+    if addend is not None:
+        addend = np.ascontiguousarray(addend, dtype=np.float64)
+        assert addend.shape == (T, H)
+    y = np.empty((T, H), dtype=np.float64)
+    lib().oracle_combine(_p(y_perm), _p(roa), _p(gate), _p(addend), T, H, K, _p(y))
+    return y
+
+
+class LayerResult:
+    def __init__(self, R, logits32, idx, gate, row_of_assign, y):
+        self.R = R
+        self.logits32 = logits32
+        self.idx = idx
+        self.gate = gate
+        self.row_of_assign = row_of_assign
+        self.y = y
+
+
+def layer_forward(x, w_router, bias, w_gate, w_up, w_down, K: int, renormalize: bool,
+                  capacity_rows: int = 0, ws_gate=None, ws_up=None, ws_down=None) -> LayerResult:
+    T, H = x.shape
+    E, F, _ = w_gate.shape
+    dt = _dt(x)
+    Fs = 0 if ws_gate is None else ws_gate.shape[0]
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    logits32 = np.empty((T, E), dtype=np.float32)
+    idx = np.empty((T, K), dtype=np.int32)
+    gate = np.empty((T, K), dtype=np.float64)
+    roa = np.empty(T * K, dtype=np.int32)
+    y = np.empty((T, H), dtype=np.float64)
+    R = lib().oracle_layer_forward(_p(x), _p(w_router), _p(bias), _p(w_gate), _p(w_up), _p(w_down),
+                                   _p(ws_gate), _p(ws_up), _p(ws_down), T, H, E, K, F, Fs,
+                                   int(bool(renormalize)), int(capacity_rows), dt,
+                                   _p(logits32), _p(idx), _p(gate), _p(roa), _p(y))
+    return LayerResult(int(R), logits32, idx, gate, roa, y)
+
+
+def dense_bruteforce(x, w_router, bias, w_gate, w_up, w_down, K: int, renormalize: bool,
+                     capacity_rows: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 1 with every expert evaluated on every token; returns (y, dense gates)."""
+    T, H = x.shape
+    E, F, _ = w_gate.shape
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    g = np.empty((T, E), dtype=np.float64)
+    y = np.empty((T, H), dtype=np.float64)
+    lib().oracle_dense_bruteforce(_p(x), _p(w_router), _p(bias), _p(w_gate), _p(w_up), _p(w_down),
+                                  T, H, E, K, F, int(bool(renormalize)), int(capacity_rows), _dt(x),
+                                  _p(g), _p(y))
+    return y, g

@@ -1,0 +1,381 @@
+/*
+ * moe_oracle.c -- slow, plain CPU oracle for the MoE-layer forward hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing in the product path may link, load or
+ * call this file; it exists so that the HIP kernels can be checked against an
+ * implementation that can be compared with the paper by eye.  It shares no
+ * code, tables or helpers with the HIP path.
+ *
+ * What it follows (arXiv 2504.14960):
+ *   Eq. 1  (Section 3.1.1)  y = sum_e g_e(x) * f_e(x)
+ *   Eq. 2  (Section 3.1.1)  Top-K gating: g_e = s_e for the K largest s, else 0
+ *   Eq. 3  (Section 3.1.1)  s = G(W_g x), G = softmax (Section 3.3, router paragraph)
+ *   Eq. 4  (Section 3.1.1)  capacity per expert = CF * L / E, over-capacity tokens dropped
+ *   Section 3.1.2 "Token Dispatching" / "Token Restore": rows of one expert
+ *   contiguous in memory; inverse permutation back to token order.
+ *   Section 3.3: sub-sequence dropping -- the drop decision uses only the
+ *   tokens of this call.
+ *
+ * The fast path (permute + grouped GEMM + unpermute) reaches Eq. 1 exactly up
+ * to rounding order, so every function below is the plain definition written
+ * out: no blocking, no fusion, no reordering.  All floating-point work is done
+ * in double; inputs are fp32 or bf16 bit patterns and are widened exactly.
+ * The one place where floating point decides an integer -- which K experts a
+ * token selects -- is taken on fp32 logits, the precision the kernels hold
+ * logits in, so both sides decide on the same numbers.
+ *
+ * Readings of points the paper leaves open (each is also listed in the
+ * design notes of this repository):
+ *   - Top-K runs over experts, per token (Eq. 2's index is garbled in print).
+ *   - Selection order: larger logit first, equal logits -> lower expert index.
+ *     -0.0 and +0.0 are equal.  NaN ranks as minus infinity.
+ *   - Gates are softmax probabilities over all E experts (Eq. 2 uses raw s);
+ *     `renormalize` optionally divides the K selected gates by their sum.
+ *   - Eq. 4's L is the number of token-expert assignments T*K (the "average
+ *     expected load" of an expert is T*K/E rows); the result is rounded up.
+ *   - Over capacity, an expert keeps its first C assignments in token order.
+ *   - Dropping does not change the remaining gates.
+ *   - Rows inside an expert's block are in ascending token order, no padding.
+ *   - f_e is a bias-free SwiGLU FFN: W_down (silu(W_gate x) * (W_up x)).
+ *   - An expert index outside [0, E) is treated as a dropped assignment.
+ *
+ * Pins (tests/test_oracle_*.py): closed forms (equal logits -> 1/E, K = E ->
+ * gates sum to 1, capacity values), E = 1 reduces to a dense MLP computed with
+ * a library matmul, stable argsort cross-check of the permutation, identity
+ * experts give permute/unpermute round trip, brute-force dense Eq. 1 below,
+ * batch-split invariance, dropped-tokens-are-zero.  No function here is
+ * "parity unpinned"; the paper prints no worked numeric example of the layer.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+/* exact widening load of element i */
+static inline double ld(const void* p, size_t i, int dt) {
+    if (dt == ORACLE_F32) return (double)((const float*)p)[i];
+    uint32_t u = ((uint32_t)((const uint16_t*)p)[i]) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static inline size_t elem_size(int dt) { return dt == ORACLE_F32 ? 4u : 2u; }
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---- Eq. 3, the linear part: logits[t,e] = sum_h x[t,h] W_g[e,h] (+ bias[e]) ---- */
+void oracle_router_logits(const void* x, const void* w_router, const float* bias,
+                          int T, int H, int E, int dt, double* logits) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t)
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int h = 0; h < H; ++h)
+                acc += ld(x, (size_t)t * H + h, dt) * ld(w_router, (size_t)e * H + h, dt);
+            if (bias) acc += (double)bias[e];
+            logits[(size_t)t * E + e] = acc;
+        }
+}
+
+/* selection order of Eq. 2's TopK: value descending, then expert index ascending */
+static inline float sel_key(float v) { return isnan(v) ? -INFINITY : v; }
+static inline int ranks_before(float a, int ia, float b, int ib) {
+    a = sel_key(a);
+    b = sel_key(b);
+    if (a > b) return 1;
+    if (a < b) return 0;
+    return ia < ib; /* equal (including -0 == +0): lower index first */
+}
+
+/* ---- Eq. 2 + Eq. 3's G: softmax over all E, then the K best experts ----
+ * logits are fp32 (the decision precision).  idx[t,k] in selection order,
+ * gate[t,k] = softmax(logits[t,:])[idx[t,k]], optionally renormalised over the
+ * K selected (sum taken in slot order).  probs (may be NULL) receives the full
+ * softmax. */
+void oracle_topk_gates(const float* logits, int T, int E, int K, int renormalize,
+                       int32_t* idx, double* gate, double* probs) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        const float* l = logits + (size_t)t * E;
+        double* p = (double*)malloc(sizeof(double) * (size_t)E);
+        char* taken = (char*)calloc((size_t)E, 1);
+        double m = -INFINITY;
+        for (int e = 0; e < E; ++e)
+            if ((double)l[e] > m) m = (double)l[e];
+        double z = 0.0;
+        for (int e = 0; e < E; ++e) {
+            p[e] = exp((double)l[e] - m);
+            z += p[e];
+        }
+        for (int e = 0; e < E; ++e) {
+            p[e] /= z;
+            if (probs) probs[(size_t)t * E + e] = p[e];
+        }
+        for (int k = 0; k < K; ++k) {
+            int best = -1;
+            for (int e = 0; e < E; ++e) {
+                if (taken[e]) continue;
+                if (best < 0 || ranks_before(l[e], e, l[best], best)) best = e;
+            }
+            taken[best] = 1;
+            idx[(size_t)t * K + k] = best;
+            gate[(size_t)t * K + k] = p[best];
+        }
+        if (renormalize) {
+            double s = 0.0;
+            for (int k = 0; k < K; ++k) s += gate[(size_t)t * K + k];
+            for (int k = 0; k < K; ++k) gate[(size_t)t * K + k] /= s;
+        }
+        free(p);
+        free(taken);
+    }
+}
+
+/* ---- Eq. 4 with L = T*K, rounded up ---- */
+int oracle_capacity(double capacity_factor, int T, int K, int E) {
+    return (int)ceil(capacity_factor * (double)T * (double)K / (double)E);
+}
+
+/* ---- Section 3.1.2 "Token Dispatching", the local part ----
+ * Walk the assignments a = t*K + k in ascending order; the j-th assignment
+ * that names expert e gets rank j inside e and is kept iff dropless
+ * (capacity <= 0) or j < capacity.  Kept rows of expert e occupy
+ * [offsets[e], offsets[e+1]) in rank order.  x_perm rows are byte copies of x
+ * rows.  r_max = number of rows x_perm / assign_of_row have room for; rows
+ * beyond the kept total get assign_of_row = -1 and are left untouched in
+ * x_perm.  Returns the kept total R. */
+int oracle_permute(const void* x, const int32_t* idx, int T, int H, int E, int K,
+                   int capacity, int dt, int r_max, void* x_perm, int32_t* counts,
+                   int32_t* offsets, int32_t* row_of_assign, int32_t* assign_of_row) {
+    const size_t row_bytes = (size_t)H * elem_size(dt);
+    int64_t* n = (int64_t*)calloc((size_t)E, sizeof(int64_t));
+    const size_t A = (size_t)T * K;
+    /* pass 1: how many assignments name each expert */
+    for (size_t a = 0; a < A; ++a) {
+        int e = idx[a];
+        if (e >= 0 && e < E) n[e]++;
+    }
+    offsets[0] = 0;
+    for (int e = 0; e < E; ++e) {
+        int64_t c = (capacity > 0 && n[e] > capacity) ? capacity : n[e];
+        counts[e] = (int32_t)c;
+        offsets[e + 1] = offsets[e] + (int32_t)c;
+    }
+    const int R = offsets[E];
+    for (int r = 0; r < r_max; ++r) assign_of_row[r] = -1;
+    /* pass 2: ranks in assignment order */
+    memset(n, 0, sizeof(int64_t) * (size_t)E);
+    for (size_t a = 0; a < A; ++a) {
+        int e = idx[a];
+        if (e < 0 || e >= E) {
+            row_of_assign[a] = -1;
+            continue;
+        }
+        int64_t rank = n[e]++;
+        if (capacity > 0 && rank >= capacity) {
+            row_of_assign[a] = -1;
+            continue;
+        }
+        int row = offsets[e] + (int)rank;
+        row_of_assign[a] = row;
+        assign_of_row[row] = (int32_t)a;
+        if (x && x_perm)
+            memcpy((char*)x_perm + (size_t)row * row_bytes,
+                   (const char*)x + (a / (size_t)K) * row_bytes, row_bytes);
+    }
+    free(n);
+    return R;
+}
+
+/* ---- f_e for one expert over n_rows rows (Section 3.1.1's f_e; SwiGLU) ----
+ * x_rows [n_rows,H]; w_gate, w_up [F,H]; w_down [H,F] (all of ONE expert).
+ * h [n_rows,F] (may be NULL) and y [n_rows,H] are double. */
+void oracle_expert_ffn_rows(const void* x_rows, int n_rows, int H, int F,
+                            const void* w_gate, const void* w_up, const void* w_down,
+                            int dt, double* h_out, double* y) {
+    if (n_rows <= 0) return;
+    double* h = h_out ? h_out : (double*)malloc(sizeof(double) * (size_t)n_rows * F);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int r = 0; r < n_rows; ++r)
+        for (int f = 0; f < F; ++f) {
+            double g = 0.0, u = 0.0;
+            for (int k = 0; k < H; ++k) {
+                double xv = ld(x_rows, (size_t)r * H + k, dt);
+                g += xv * ld(w_gate, (size_t)f * H + k, dt);
+                u += xv * ld(w_up, (size_t)f * H + k, dt);
+            }
+            double silu = g / (1.0 + exp(-g));
+            h[(size_t)r * F + f] = silu * u;
+        }
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int r = 0; r < n_rows; ++r)
+        for (int n = 0; n < H; ++n) {
+            double acc = 0.0;
+            for (int f = 0; f < F; ++f)
+                acc += h[(size_t)r * F + f] * ld(w_down, (size_t)n * F + f, dt);
+            y[(size_t)r * H + n] = acc;
+        }
+    if (!h_out) free(h);
+}
+
+/* ---- "Expert Computation": every expert over its contiguous rows ---- */
+void oracle_experts(const void* x_perm, const int32_t* offsets, int E, int H, int F,
+                    const void* w_gate, const void* w_up, const void* w_down, int dt,
+                    double* h_out, double* y_perm) {
+    const size_t es = elem_size(dt);
+    for (int e = 0; e < E; ++e) {
+        int lo = offsets[e], hi = offsets[e + 1];
+        if (hi <= lo) continue;
+        oracle_expert_ffn_rows((const char*)x_perm + (size_t)lo * H * es, hi - lo, H, F,
+                               (const char*)w_gate + (size_t)e * F * H * es,
+                               (const char*)w_up + (size_t)e * F * H * es,
+                               (const char*)w_down + (size_t)e * H * F * es, dt,
+                               h_out ? h_out + (size_t)lo * F : NULL,
+                               y_perm + (size_t)lo * H);
+    }
+}
+
+/* ---- "Token Restore" + Eq. 1's weighted sum ----
+ * y[t,:] = sum over k ascending of gate[t,k] * y_perm[row_of_assign[t,k],:]
+ * (dropped assignments contribute nothing) (+ addend[t,:]). */
+void oracle_combine(const double* y_perm, const int32_t* row_of_assign, const double* gate,
+                    const double* addend, int T, int H, int K, double* y) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t)
+        for (int n = 0; n < H; ++n) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) {
+                int row = row_of_assign[(size_t)t * K + k];
+                if (row < 0) continue;
+                acc += gate[(size_t)t * K + k] * y_perm[(size_t)row * H + n];
+            }
+            if (addend) acc += addend[(size_t)t * H + n];
+            y[(size_t)t * H + n] = acc;
+        }
+}
+
+/* ---- the whole layer through the dispatcher's data path ----
+ * shared expert (ws_* non-NULL, Fs > 0): y += f_shared(x) for every token,
+ * ungated.  Optional outputs may be NULL.  Returns R. */
+int oracle_layer_forward(const void* x, const void* w_router, const float* bias,
+                         const void* w_gate, const void* w_up, const void* w_down,
+                         const void* ws_gate, const void* ws_up, const void* ws_down,
+                         int T, int H, int E, int K, int F, int Fs, int renormalize,
+                         int capacity, int dt, float* logits32_out, int32_t* idx_out,
+                         double* gate_out, int32_t* row_of_assign_out, double* y) {
+    const size_t A = (size_t)T * K;
+    double* logits = (double*)malloc(sizeof(double) * (size_t)T * E);
+    float* l32 = (float*)malloc(sizeof(float) * (size_t)T * E);
+    int32_t* idx = (int32_t*)malloc(sizeof(int32_t) * A);
+    double* gate = (double*)malloc(sizeof(double) * A);
+    oracle_router_logits(x, w_router, bias, T, H, E, dt, logits);
+    for (size_t i = 0; i < (size_t)T * E; ++i) l32[i] = (float)logits[i];
+    oracle_topk_gates(l32, T, E, K, renormalize, idx, gate, NULL);
+
+    int r_max = (int)A;
+    void* x_perm = malloc((size_t)r_max * H * elem_size(dt) + 1);
+    int32_t* counts = (int32_t*)malloc(sizeof(int32_t) * (size_t)E);
+    int32_t* offsets = (int32_t*)malloc(sizeof(int32_t) * (size_t)(E + 1));
+    int32_t* roa = (int32_t*)malloc(sizeof(int32_t) * A);
+    int32_t* aor = (int32_t*)malloc(sizeof(int32_t) * (size_t)r_max + 4);
+    int R = oracle_permute(x, idx, T, H, E, K, capacity, dt, r_max, x_perm, counts, offsets, roa, aor);
+
+    double* y_perm = (double*)malloc(sizeof(double) * ((size_t)R * H + 1));
+    oracle_experts(x_perm, offsets, E, H, F, w_gate, w_up, w_down, dt, NULL, y_perm);
+
+    double* shared = NULL;
+    if (Fs > 0 && ws_gate && ws_up && ws_down) {
+        shared = (double*)malloc(sizeof(double) * (size_t)T * H);
+        oracle_expert_ffn_rows(x, T, H, Fs, ws_gate, ws_up, ws_down, dt, NULL, shared);
+    }
+    oracle_combine(y_perm, roa, gate, shared, T, H, K, y);
+
+    if (logits32_out) memcpy(logits32_out, l32, sizeof(float) * (size_t)T * E);
+    if (idx_out) memcpy(idx_out, idx, sizeof(int32_t) * A);
+    if (gate_out) memcpy(gate_out, gate, sizeof(double) * A);
+    if (row_of_assign_out) memcpy(row_of_assign_out, roa, sizeof(int32_t) * A);
+    free(logits); free(l32); free(idx); free(gate); free(x_perm); free(counts);
+    free(offsets); free(roa); free(aor); free(y_perm); free(shared);
+    return R;
+}
+
+/* ---- Eq. 1 literally, with no permutation anywhere (tiny inputs only) ----
+ * Builds the dense gate matrix g[T,E] (zero for unselected and for dropped),
+ * evaluates EVERY expert on EVERY token and sums g[t,e] * f_e(x_t).  The
+ * selection here is a full sort of (logit, index) pairs and the capacity rule
+ * is applied per expert by walking tokens, so it shares no logic with
+ * oracle_topk_gates / oracle_permute above. */
+typedef struct { float v; int e; } pair_t;
+static int pair_cmp(const void* a, const void* b) {
+    const pair_t* p = (const pair_t*)a;
+    const pair_t* q = (const pair_t*)b;
+    float pv = isnan(p->v) ? -INFINITY : p->v, qv = isnan(q->v) ? -INFINITY : q->v;
+    if (pv > qv) return -1;
+    if (pv < qv) return 1;
+    return (p->e > q->e) - (p->e < q->e);
+}
+
+void oracle_dense_bruteforce(const void* x, const void* w_router, const float* bias,
+                             const void* w_gate, const void* w_up, const void* w_down,
+                             int T, int H, int E, int K, int F, int renormalize,
+                             int capacity, int dt, double* g_dense_out, double* y) {
+    const size_t es = elem_size(dt);
+    double* g = (double*)calloc((size_t)T * E, sizeof(double));
+    char* sel = (char*)calloc((size_t)T * E, 1);
+    pair_t* pr = (pair_t*)malloc(sizeof(pair_t) * (size_t)E);
+    for (int t = 0; t < T; ++t) {
+        double m = -INFINITY, z = 0.0;
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int h = 0; h < H; ++h)
+                acc += ld(x, (size_t)t * H + h, dt) * ld(w_router, (size_t)e * H + h, dt);
+            if (bias) acc += (double)bias[e];
+            pr[e].v = (float)acc;
+            pr[e].e = e;
+            if ((double)pr[e].v > m) m = (double)pr[e].v;
+        }
+        for (int e = 0; e < E; ++e) z += exp((double)pr[e].v - m);
+        qsort(pr, (size_t)E, sizeof(pair_t), pair_cmp);
+        double s = 0.0;
+        for (int k = 0; k < K; ++k) {
+            g[(size_t)t * E + pr[k].e] = exp((double)pr[k].v - m) / z;
+            sel[(size_t)t * E + pr[k].e] = 1;
+            s += g[(size_t)t * E + pr[k].e];
+        }
+        if (renormalize)
+            for (int k = 0; k < K; ++k) g[(size_t)t * E + pr[k].e] /= s;
+    }
+    if (capacity > 0)
+        for (int e = 0; e < E; ++e) {
+            int seen = 0;
+            for (int t = 0; t < T; ++t)
+                if (sel[(size_t)t * E + e]) {
+                    if (seen >= capacity) g[(size_t)t * E + e] = 0.0;
+                    ++seen;
+                }
+        }
+    double* fe = (double*)malloc(sizeof(double) * (size_t)H);
+    for (int t = 0; t < T; ++t) {
+        for (int n = 0; n < H; ++n) y[(size_t)t * H + n] = 0.0;
+        for (int e = 0; e < E; ++e) {
+            oracle_expert_ffn_rows((const char*)x + (size_t)t * H * es, 1, H, F,
+                                   (const char*)w_gate + (size_t)e * F * H * es,
+                                   (const char*)w_up + (size_t)e * F * H * es,
+                                   (const char*)w_down + (size_t)e * H * F * es, dt, NULL, fe);
+            for (int n = 0; n < H; ++n) y[(size_t)t * H + n] += g[(size_t)t * E + e] * fe[n];
+        }
+    }
+    if (g_dense_out) memcpy(g_dense_out, g, sizeof(double) * (size_t)T * E);
+    free(fe); free(pr); free(g); free(sel);
+}
