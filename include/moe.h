@@ -1,0 +1,211 @@
+/*
+ * moe.h -- C ABI of the MI355X (gfx950) MoE-layer forward hot path.
+ *
+ * The library computes, on one GPU with all experts local, the forward of the
+ * Mixture-of-Experts layer of arXiv 2504.14960:
+ *
+ *     y = sum_e g_e(x) * f_e(x)                       (Eq. 1, Section 3.1.1)
+ *
+ * through the data path of the paper's token dispatcher (Section 3.3, forward
+ * workflow, with EP = ETP = 1 so that every collective drops out):
+ *
+ *     router -> permute -> experts -> un-permute
+ *
+ * Notation: T tokens, H hidden size, E experts, K experts per token, F expert
+ * FFN size, C capacity (rows per expert, 0 = dropless), R kept rows.
+ *
+ * Conventions common to every entry point
+ *   - Every tensor pointer is DEVICE memory owned by the caller, row-major,
+ *     innermost dimension contiguous, 16-byte aligned.  The library never
+ *     allocates, frees or retains device memory; scratch comes in as
+ *     `workspace`.  `moe_last_error` is the only pointer it hands out.
+ *   - `stream` is a hipStream_t owned by the caller (NULL = the default
+ *     stream).  All work is enqueued on it; nothing synchronises; outputs are
+ *     valid in stream order.  No host<->device copies happen: per-expert row
+ *     counts stay on the device.
+ *   - Weights are [out_features, in_features] (the contraction index is the
+ *     contiguous one for both operands).
+ *   - dt is the storage type of x, the weights, x_perm, h, y_perm and y.
+ *     Logits, gates and all accumulation are fp32 for both types.
+ *   - Argument errors are detected on the host before anything is enqueued and
+ *     returned as a status; `moe_last_error()` then holds a message.  Device
+ *     data is never validated on the host: an expert index outside [0, E) is
+ *     treated as a dropped assignment, never as an address.
+ *   - T == 0 is legal (MOE_OK, nothing launched).  Experts with no rows are
+ *     legal everywhere.
+ *   - Same inputs give bit-identical outputs on every call (no floating-point
+ *     atomics, no slot-claiming atomics).
+ *   - Limits: 1 <= K <= min(E, 64), E <= 256, T*K < 2^31, H % 8 == 0 and
+ *     F % 8 == 0 for MOE_BF16 (H % 4, F % 4 for MOE_F32).
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = 1, /* NULL where not allowed, bad size, misalignment */
+    MOE_ERR_UNSUPPORTED = 2, /* a legal request outside the limits above */
+    MOE_ERR_WORKSPACE = 3,   /* workspace NULL or too small */
+    MOE_ERR_LAUNCH = 4       /* the HIP runtime refused a launch */
+} moe_status_t;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
+
+typedef void* moe_stream_t;
+
+/* Message of the last failed call on this host thread ("" if none).  Static
+ * thread-local storage; never free it. */
+const char* moe_last_error(void);
+
+/* Library version string (static storage). */
+const char* moe_version(void);
+
+/* Eq. 4 (Section 3.1.1): capacity per expert = CF * L / E, with L = T*K
+ * token-expert assignments, rounded up.  Host only, pure.  Returns 0 when
+ * capacity_factor <= 0 (dropless). */
+int moe_capacity_from_factor(double capacity_factor, int T, int K, int E);
+
+/* Rows x_perm / y_perm / h / assign_of_row must have room for:
+ * T*K when dropless (capacity <= 0), else min(T*K, E*capacity).  Host only. */
+int moe_max_rows(int T, int K, int E, int capacity);
+
+/* Bytes of scratch moe_permute needs.  Host only. */
+size_t moe_permute_workspace_bytes(int T, int K, int E);
+
+/*
+ * a1. Router: Eq. 3 (s = softmax(W_g x)) and Eq. 2 (Top-K gating), Section
+ * 3.1.1; "selecting the top-k ... based on their softmax probabilities",
+ * Section 3.3.
+ *
+ *   logits[t,e] = sum_h x[t,h] * w_router[e,h] (+ logit_bias[e])     fp32
+ *   the K experts with the largest logits are selected, slot order = logit
+ *   descending, equal logits -> lower expert index first (-0 == +0, NaN ranks
+ *   last); topk_gate[t,k] = softmax(logits[t,:])[topk_idx[t,k]], divided by
+ *   the sum of the K selected gates when renormalize != 0.
+ *
+ * x [T,H] (dt), w_router [E,H] (dt), logit_bias [E] fp32 or NULL.
+ * logits [T,E] fp32: OUTPUT when x != NULL.  When x == NULL the product is
+ * skipped and `logits` is the INPUT the selection runs on (w_router,
+ * logit_bias, H are then ignored).
+ * topk_idx [T,K] int32, topk_gate [T,K] fp32: outputs.
+ */
+moe_status_t moe_router_topk(const void* x, const void* w_router, const float* logit_bias,
+                             float* logits, int T, int H, int E, int K, int renormalize,
+                             moe_dtype_t dt, int32_t* topk_idx, float* topk_gate,
+                             moe_stream_t stream);
+
+/*
+ * a2. Permute: Section 3.1.2 "Token Dispatching" (tokens of one expert stored
+ * contiguously) with the capacity rule of Eq. 4 / Section 3.3 (sub-sequence
+ * dropping: only this call's tokens decide).
+ *
+ * Assignments a = t*K + k are ranked inside their expert in ascending a; an
+ * assignment is kept iff capacity <= 0 or its rank < capacity.  Kept rows of
+ * expert e occupy rows [expert_offsets[e], expert_offsets[e+1]) of x_perm in
+ * rank order; x_perm[row,:] is a byte copy of x[t,:].
+ *
+ * x [T,H] (dt), topk_idx [T,K] int32 -> x_perm [R_max,H] (dt; rows >= R are
+ * left untouched), expert_counts [E], expert_offsets [E+1], row_of_assign
+ * [T*K] (-1 = dropped), assign_of_row [R_max] (-1 = unused), all int32, with
+ * R_max = moe_max_rows(T,K,E,capacity).  workspace: at least
+ * moe_permute_workspace_bytes(T,K,E) bytes, contents irrelevant on entry.
+ * x and x_perm may both be NULL to compute the maps only.
+ */
+moe_status_t moe_permute(const void* x, const int32_t* topk_idx, int T, int H, int E, int K,
+                         int capacity, moe_dtype_t dt, void* x_perm, int32_t* expert_counts,
+                         int32_t* expert_offsets, int32_t* row_of_assign,
+                         int32_t* assign_of_row, void* workspace, size_t workspace_bytes,
+                         moe_stream_t stream);
+
+/*
+ * a3. Experts: Section 3.1.2 "Expert Computation"; f_e of Eq. 1 as a bias-free
+ * SwiGLU FFN (the paper leaves f_e open):
+ *
+ *   h[r,:]      = silu(x_perm[r,:] W_gate,e^T) * (x_perm[r,:] W_up,e^T)
+ *   y_perm[r,:] = h[r,:] W_down,e^T          for r in expert e's row range
+ *
+ * x_perm [R_max,H] (dt); expert_offsets [E+1] int32 in DEVICE memory (rows of
+ * expert e = [offsets[e], offsets[e+1]), offsets[E] <= R_max, non-decreasing);
+ * w_gate, w_up [E,F,H]; w_down [E,H,F]; h_workspace [R_max,F] (dt, scratch and
+ * output: h is rounded to dt once); y_perm [R_max,H] (dt).  Rows >= offsets[E]
+ * of h and y_perm are left untouched.  Accumulation is fp32; silu(z) =
+ * z / (1 + exp(-z)) in fp32.
+ */
+moe_status_t moe_grouped_gemm_swiglu(const void* x_perm, const int32_t* expert_offsets, int R_max,
+                                     int H, int F, int E, const void* w_gate, const void* w_up,
+                                     const void* w_down, moe_dtype_t dt, void* h_workspace,
+                                     void* y_perm, moe_stream_t stream);
+
+/* The two halves of a3 as separate calls (same kernels, same arguments), so
+ * that a caller can time or overlap them:
+ *   moe_expert_gate_up:  h = silu(x_perm W_gate^T) * (x_perm W_up^T)
+ *   moe_expert_down:     y_perm = h W_down^T
+ * moe_grouped_gemm_swiglu is exactly gate_up followed by down. */
+moe_status_t moe_expert_gate_up(const void* x_perm, const int32_t* expert_offsets, int R_max, int H,
+                                int F, int E, const void* w_gate, const void* w_up, moe_dtype_t dt,
+                                void* h, moe_stream_t stream);
+moe_status_t moe_expert_down(const void* h, const int32_t* expert_offsets, int R_max, int H, int F,
+                             int E, const void* w_down, moe_dtype_t dt, void* y_perm,
+                             moe_stream_t stream);
+
+/*
+ * a4. Un-permute + combine: Section 3.1.2 "Token Restore" and the weighted sum
+ * of Eq. 1:
+ *
+ *   y[t,:] = sum_{k ascending, row_of_assign[t*K+k] >= 0}
+ *                topk_gate[t,k] * y_perm[row_of_assign[t*K+k],:]  (+ addend[t,:])
+ *
+ * accumulated in fp32 and rounded to dt once.  A token whose assignments were
+ * all dropped gets exactly 0 (+ addend).  y_perm [R_max,H] (dt), row_of_assign
+ * [T*K] int32 (each entry < R_max or negative), topk_gate [T,K] fp32, addend
+ * [T,H] (dt) or NULL, y [T,H] (dt).
+ */
+moe_status_t moe_unpermute_combine(const void* y_perm, const int32_t* row_of_assign,
+                                   const float* topk_gate, const void* addend, int T, int H,
+                                   int K, int R_max, moe_dtype_t dt, void* y, moe_stream_t stream);
+
+/* Bytes of workspace moe_layer_forward needs.  Fs = FFN size of the shared
+ * expert (0 = none).  Host only. */
+size_t moe_layer_workspace_bytes(int T, int H, int E, int K, int F, int Fs, int capacity,
+                                 moe_dtype_t dt);
+
+/* Where moe_layer_forward keeps its intermediates inside `workspace`, for
+ * tests and profiling.  Writes 11 byte offsets into byte_offsets[0..10], in
+ * this order: logits [T,E] f32, topk_idx [T,K] i32, topk_gate [T,K] f32,
+ * expert_counts [E] i32, expert_offsets [E+1] i32, row_of_assign [T*K] i32,
+ * assign_of_row [R_max] i32, x_perm [R_max,H] dt, h [R_max,F] dt,
+ * y_perm [R_max,H] dt, shared-expert output [T,H] dt.  n = capacity of
+ * byte_offsets (>= 11).  Host only. */
+moe_status_t moe_layer_workspace_layout(int T, int H, int E, int K, int F, int Fs, int capacity,
+                                        moe_dtype_t dt, size_t* byte_offsets, int n);
+
+/*
+ * The whole forward of Section 3.3 on one stream: a1 -> a2 -> a3 -> a4, plus an
+ * optional always-on shared expert (ws_* non-NULL and Fs > 0) that is evaluated
+ * on x directly and added, ungated, in a4.  The throughput metric times this
+ * call.  y [T,H] (dt) is the only user-visible output; intermediates live in
+ * `workspace` (layout private, see moe_layer_workspace_bytes).
+ */
+moe_status_t moe_layer_forward(const void* x, const void* w_router, const float* logit_bias,
+                               const void* w_gate, const void* w_up, const void* w_down,
+                               const void* ws_gate, const void* ws_up, const void* ws_down,
+                               int T, int H, int E, int K, int F, int Fs, int renormalize,
+                               int capacity, moe_dtype_t dt, void* y, void* workspace,
+                               size_t workspace_bytes, moe_stream_t stream);
+
+/* Tuning knobs for experiments (process-wide, not thread-safe; defaults are
+ * the tuned ones).  Unknown names return MOE_ERR_INVALID_ARG.  Names:
+ * "gemm_variant" (0 = auto). */
+moe_status_t moe_set_option(const char* name, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

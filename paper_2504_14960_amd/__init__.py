@@ -1,0 +1,27 @@
+"""MI355X-native MoE-layer forward hot path (arXiv 2504.14960, Section 3.3).
+
+A thin ctypes binding over ``libmoe_hip.so``; every step of the path (router,
+permute, grouped SwiGLU expert GEMMs, un-permute/combine) runs in the HIP
+kernels of ``csrc/``.  PyTorch is used for device memory and streams only.
+"""
+from .binding import (  # noqa: F401
+    MOE_BF16,
+    MOE_F32,
+    MoeError,
+    capacity_from_factor,
+    expert_down,
+    expert_gate_up,
+    grouped_gemm_swiglu,
+    layer_forward,
+    layer_workspace_bytes,
+    layer_workspace_layout,
+    lib,
+    lib_path,
+    max_rows,
+    permute,
+    permute_workspace_bytes,
+    router_topk,
+    set_option,
+    unpermute_combine,
+    version,
+)

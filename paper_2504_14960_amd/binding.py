@@ -1,0 +1,210 @@
+"""ctypes binding of include/moe.h: argument marshalling only.
+
+Functions take torch tensors that already live on the GPU, pass their device
+pointers and the current stream to the C ABI and return nothing that was
+computed on the host.  There is no fallback: if the HIP library is missing the
+import of a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+MOE_F32 = 0
+MOE_BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
+_lib = None
+
+
+class MoeError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"moe status {status}: {message}")
+        self.status = status
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> C.CDLL:
+    """Load libmoe_hip.so (built by ``python -m paper_2504_14960_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2504_14960_amd.build` "
+            "(there is no non-HIP fallback)")
+    L = C.CDLL(_LIB_PATH)
+    vp, i, f, sz = C.c_void_p, C.c_int, C.c_double, C.c_size_t
+    L.moe_last_error.restype = C.c_char_p
+    L.moe_last_error.argtypes = []
+    L.moe_version.restype = C.c_char_p
+    L.moe_version.argtypes = []
+    L.moe_capacity_from_factor.restype = i
+    L.moe_capacity_from_factor.argtypes = [f, i, i, i]
+    L.moe_max_rows.restype = i
+    L.moe_max_rows.argtypes = [i, i, i, i]
+    L.moe_permute_workspace_bytes.restype = sz
+    L.moe_permute_workspace_bytes.argtypes = [i, i, i]
+    L.moe_router_topk.restype = i
+    L.moe_router_topk.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp]
+    L.moe_permute.restype = i
+    L.moe_permute.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moe_grouped_gemm_swiglu.restype = i
+    L.moe_grouped_gemm_swiglu.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, i, vp, vp, vp]
+    L.moe_expert_gate_up.restype = i
+    L.moe_expert_gate_up.argtypes = [vp, vp, i, i, i, i, vp, vp, i, vp, vp]
+    L.moe_expert_down.restype = i
+    L.moe_expert_down.argtypes = [vp, vp, i, i, i, i, vp, i, vp, vp]
+    L.moe_unpermute_combine.restype = i
+    L.moe_unpermute_combine.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, vp]
+    L.moe_layer_workspace_bytes.restype = sz
+    L.moe_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
+    L.moe_layer_workspace_layout.restype = i
+    L.moe_layer_workspace_layout.argtypes = [i, i, i, i, i, i, i, i, C.POINTER(sz), i]
+    L.moe_layer_forward.restype = i
+    L.moe_layer_forward.argtypes = [vp] * 9 + [i] * 9 + [vp, vp, sz, vp]
+    L.moe_set_option.restype = i
+    L.moe_set_option.argtypes = [C.c_char_p, i]
+    _lib = L
+    return L
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise MoeError(status, lib().moe_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("the MoE hot path takes device tensors only")
+    if not t.is_contiguous():
+        raise ValueError("tensors must be contiguous")
+    return t.data_ptr()
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return MOE_BF16
+    if t.dtype == torch.float32:
+        return MOE_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def version() -> str:
+    return lib().moe_version().decode()
+
+
+def set_option(name: str, value: int) -> None:
+    _check(lib().moe_set_option(name.encode(), int(value)))
+
+
+def capacity_from_factor(cf: float, T: int, K: int, E: int) -> int:
+    return int(lib().moe_capacity_from_factor(float(cf), T, K, E))
+
+
+def max_rows(T: int, K: int, E: int, capacity: int) -> int:
+    return int(lib().moe_max_rows(T, K, E, capacity))
+
+
+def permute_workspace_bytes(T: int, K: int, E: int) -> int:
+    return int(lib().moe_permute_workspace_bytes(T, K, E))
+
+
+def router_topk(x: Optional[torch.Tensor], w_router: Optional[torch.Tensor],
+                logit_bias: Optional[torch.Tensor], logits: torch.Tensor, K: int, renormalize: bool,
+                topk_idx: torch.Tensor, topk_gate: torch.Tensor, dtype: Optional[int] = None) -> None:
+    T, E = logits.shape
+    H = x.shape[1] if x is not None else 0
+    dt = _dt(x) if x is not None else (MOE_BF16 if dtype is None else dtype)
+    _check(lib().moe_router_topk(_ptr(x), _ptr(w_router), _ptr(logit_bias), _ptr(logits), T, H, E, K,
+                                 int(bool(renormalize)), dt, _ptr(topk_idx), _ptr(topk_gate), _stream()))
+
+
+def permute(x: Optional[torch.Tensor], topk_idx: torch.Tensor, E: int, capacity: int,
+            x_perm: Optional[torch.Tensor], expert_counts: torch.Tensor, expert_offsets: torch.Tensor,
+            row_of_assign: torch.Tensor, assign_of_row: torch.Tensor, workspace: torch.Tensor,
+            H: Optional[int] = None, dtype: int = MOE_BF16) -> None:
+    T, K = topk_idx.shape
+    if x is not None:
+        H, dtype = x.shape[1], _dt(x)
+    elif H is None:
+        H = 8
+    _check(lib().moe_permute(_ptr(x), _ptr(topk_idx), T, H, E, K, int(capacity), dtype, _ptr(x_perm),
+                             _ptr(expert_counts), _ptr(expert_offsets), _ptr(row_of_assign),
+                             _ptr(assign_of_row), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                             _stream()))
+
+
+def grouped_gemm_swiglu(x_perm: torch.Tensor, expert_offsets: torch.Tensor, w_gate: torch.Tensor,
+                        w_up: torch.Tensor, w_down: torch.Tensor, h_workspace: torch.Tensor,
+                        y_perm: torch.Tensor) -> None:
+    R_max, H = x_perm.shape
+    E, F, _ = w_gate.shape
+    _check(lib().moe_grouped_gemm_swiglu(_ptr(x_perm), _ptr(expert_offsets), R_max, H, F, E, _ptr(w_gate),
+                                         _ptr(w_up), _ptr(w_down), _dt(x_perm), _ptr(h_workspace),
+                                         _ptr(y_perm), _stream()))
+
+
+def expert_gate_up(x_perm: torch.Tensor, expert_offsets: torch.Tensor, w_gate: torch.Tensor,
+                   w_up: torch.Tensor, h: torch.Tensor) -> None:
+    R_max, H = x_perm.shape
+    E, F, _ = w_gate.shape
+    _check(lib().moe_expert_gate_up(_ptr(x_perm), _ptr(expert_offsets), R_max, H, F, E, _ptr(w_gate),
+                                    _ptr(w_up), _dt(x_perm), _ptr(h), _stream()))
+
+
+def expert_down(h: torch.Tensor, expert_offsets: torch.Tensor, w_down: torch.Tensor,
+                y_perm: torch.Tensor) -> None:
+    R_max, F = h.shape
+    E, H, _ = w_down.shape
+    _check(lib().moe_expert_down(_ptr(h), _ptr(expert_offsets), R_max, H, F, E, _ptr(w_down), _dt(h),
+                                 _ptr(y_perm), _stream()))
+
+
+def unpermute_combine(y_perm: torch.Tensor, row_of_assign: torch.Tensor, topk_gate: torch.Tensor,
+                      addend: Optional[torch.Tensor], y: torch.Tensor) -> None:
+    T, K = topk_gate.shape
+    R_max, H = y_perm.shape
+    _check(lib().moe_unpermute_combine(_ptr(y_perm), _ptr(row_of_assign), _ptr(topk_gate), _ptr(addend),
+                                       T, H, K, R_max, _dt(y), _ptr(y), _stream()))
+
+
+def layer_workspace_bytes(T: int, H: int, E: int, K: int, F: int, Fs: int, capacity: int, dtype: int) -> int:
+    return int(lib().moe_layer_workspace_bytes(T, H, E, K, F, Fs, capacity, dtype))
+
+
+_LAYOUT_NAMES = ("logits", "topk_idx", "topk_gate", "expert_counts", "expert_offsets", "row_of_assign",
+                 "assign_of_row", "x_perm", "h", "y_perm", "shared_y")
+
+
+def layer_workspace_layout(T: int, H: int, E: int, K: int, F: int, Fs: int, capacity: int, dtype: int) -> dict:
+    arr = (C.c_size_t * 11)()
+    _check(lib().moe_layer_workspace_layout(T, H, E, K, F, Fs, capacity, dtype, arr, 11))
+    return dict(zip(_LAYOUT_NAMES, (int(v) for v in arr)))
+
+
+def layer_forward(x: torch.Tensor, w_router: torch.Tensor, logit_bias: Optional[torch.Tensor],
+                  w_gate: torch.Tensor, w_up: torch.Tensor, w_down: torch.Tensor,
+                  ws_gate: Optional[torch.Tensor], ws_up: Optional[torch.Tensor],
+                  ws_down: Optional[torch.Tensor], K: int, renormalize: bool, capacity: int,
+                  y: torch.Tensor, workspace: torch.Tensor) -> None:
+    T, H = x.shape
+    E, F, _ = w_gate.shape
+    Fs = 0 if ws_gate is None else ws_gate.shape[0]
+    _check(lib().moe_layer_forward(_ptr(x), _ptr(w_router), _ptr(logit_bias), _ptr(w_gate), _ptr(w_up),
+                                   _ptr(w_down), _ptr(ws_gate), _ptr(ws_up), _ptr(ws_down), T, H, E, K, F,
+                                   Fs, int(bool(renormalize)), int(capacity), _dt(x), _ptr(y),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))

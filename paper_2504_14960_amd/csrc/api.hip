@@ -1,0 +1,311 @@
+// C ABI of the MoE hot path: host-side argument validation and kernel launches.
+// Nothing here touches device data, allocates, or synchronises.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <cmath>
+
+#include "common.h"
+
+namespace moe {
+
+static thread_local char g_err[512] = "";
+static int g_gemm_variant = 0;
+
+moe_status_t fail(moe_status_t st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+moe_status_t check_launch(const char* what) {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(MOE_ERR_LAUNCH, "%s: %s", what, hipGetErrorString(e));
+    return MOE_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static moe_status_t check_dims(const char* fn, int T, int H, int E, int K, moe_dtype_t dt) {
+    if (dt != MOE_F32 && dt != MOE_BF16) return fail(MOE_ERR_INVALID_ARG, "%s: unknown dtype %d", fn, (int)dt);
+    if (T < 0 || H <= 0 || E <= 0 || K <= 0)
+        return fail(MOE_ERR_INVALID_ARG, "%s: need T >= 0, H, E, K > 0 (T=%d H=%d E=%d K=%d)", fn, T, H, E, K);
+    if (K > E) return fail(MOE_ERR_INVALID_ARG, "%s: K=%d exceeds E=%d", fn, K, E);
+    if (E > kMaxExperts) return fail(MOE_ERR_UNSUPPORTED, "%s: E=%d exceeds the limit %d", fn, E, kMaxExperts);
+    if (K > kMaxTopK) return fail(MOE_ERR_UNSUPPORTED, "%s: K=%d exceeds the limit %d", fn, K, kMaxTopK);
+    if ((long long)T * K >= (1ll << 31)) return fail(MOE_ERR_UNSUPPORTED, "%s: T*K must be below 2^31", fn);
+    const int vec = (dt == MOE_BF16) ? 8 : 4;
+    if (H % vec != 0) return fail(MOE_ERR_UNSUPPORTED, "%s: H=%d must be a multiple of %d", fn, H, vec);
+    return MOE_OK;
+}
+
+#define REQUIRE_PTR(fn, p)                                                                    \
+    do {                                                                                      \
+        if ((p) == nullptr) return fail(MOE_ERR_INVALID_ARG, "%s: %s is NULL", fn, #p);       \
+        if (!aligned16(p)) return fail(MOE_ERR_INVALID_ARG, "%s: %s is not 16-byte aligned", fn, #p); \
+    } while (0)
+
+struct LayerLayout {
+    size_t logits, idx, gate, counts, offsets, roa, aor, perm_ws, x_perm, h, y_perm;
+    size_t s_offsets, s_h, s_y, total;
+    int r_max;
+};
+
+static size_t up256(size_t v) { return (v + 255) & ~size_t(255); }
+
+static LayerLayout layer_layout(int T, int H, int E, int K, int F, int Fs, int capacity, moe_dtype_t dt) {
+    LayerLayout L;
+    const size_t es = (dt == MOE_BF16) ? 2 : 4;
+    const size_t A = (size_t)T * K;
+    L.r_max = moe_max_rows(T, K, E, capacity);
+    const size_t R = (size_t)L.r_max;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { const size_t at = o; o = up256(o + bytes); return at; };
+    L.logits = take((size_t)T * E * 4);
+    L.idx = take(A * 4);
+    L.gate = take(A * 4);
+    L.counts = take((size_t)E * 4);
+    L.offsets = take((size_t)(E + 1) * 4);
+    L.roa = take(A * 4);
+    L.aor = take(R * 4);
+    L.perm_ws = take(permute_workspace_bytes(T, K, E));
+    L.x_perm = take(R * H * es);
+    L.h = take(R * F * es);
+    L.y_perm = take(R * H * es);
+    L.s_offsets = take(2 * 4);
+    L.s_h = take(Fs > 0 ? (size_t)T * Fs * es : 0);
+    L.s_y = take(Fs > 0 ? (size_t)T * H * es : 0);
+    L.total = o;
+    return L;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+const char* moe_last_error(void) { return g_err; }
+
+const char* moe_version(void) { return "moe-hotpath-gfx950 0.1"; }
+
+int moe_capacity_from_factor(double capacity_factor, int T, int K, int E) {
+    if (!(capacity_factor > 0.0) || E <= 0) return 0;
+    return (int)std::ceil(capacity_factor * (double)T * (double)K / (double)E);
+}
+
+int moe_max_rows(int T, int K, int E, int capacity) {
+    const long long A = (long long)T * K;
+    if (capacity <= 0) return (int)A;
+    const long long cap = (long long)E * capacity;
+    return (int)(A < cap ? A : cap);
+}
+
+size_t moe_permute_workspace_bytes(int T, int K, int E) {
+    if (T < 0 || K <= 0 || E <= 0) return 0;
+    return permute_workspace_bytes(T, K, E);
+}
+
+moe_status_t moe_router_topk(const void* x, const void* w_router, const float* logit_bias,
+                             float* logits, int T, int H, int E, int K, int renormalize,
+                             moe_dtype_t dt, int32_t* topk_idx, float* topk_gate,
+                             moe_stream_t stream) {
+    static const char* fn = "moe_router_topk";
+    if (x == nullptr) H = (dt == MOE_BF16) ? 8 : 4;  // ignored, keep the shape check quiet
+    if (moe_status_t st = check_dims(fn, T, H, E, K, dt)) return st;
+    if (T == 0) return MOE_OK;
+    REQUIRE_PTR(fn, logits);
+    REQUIRE_PTR(fn, topk_idx);
+    REQUIRE_PTR(fn, topk_gate);
+    if (x != nullptr) {
+        REQUIRE_PTR(fn, x);
+        REQUIRE_PTR(fn, w_router);
+        if (logit_bias && (reinterpret_cast<uintptr_t>(logit_bias) & 3u))
+            return fail(MOE_ERR_INVALID_ARG, "%s: logit_bias is not 4-byte aligned", fn);
+    }
+    launch_router(x, w_router, x ? logit_bias : nullptr, logits, T, H, E, K, renormalize != 0, dt,
+                  topk_idx, topk_gate, static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
+moe_status_t moe_permute(const void* x, const int32_t* topk_idx, int T, int H, int E, int K,
+                         int capacity, moe_dtype_t dt, void* x_perm, int32_t* expert_counts,
+                         int32_t* expert_offsets, int32_t* row_of_assign,
+                         int32_t* assign_of_row, void* workspace, size_t workspace_bytes,
+                         moe_stream_t stream) {
+    static const char* fn = "moe_permute";
+    if (moe_status_t st = check_dims(fn, T, H, E, K, dt)) return st;
+    if ((x == nullptr) != (x_perm == nullptr))
+        return fail(MOE_ERR_INVALID_ARG, "%s: x and x_perm must both be given or both be NULL", fn);
+    REQUIRE_PTR(fn, expert_counts);
+    REQUIRE_PTR(fn, expert_offsets);
+    if (T == 0) {
+        // nothing routed: all experts empty
+        launch_fill_i32(expert_counts, E, 0, 0, static_cast<hipStream_t>(stream));
+        launch_fill_i32(expert_offsets, E + 1, 0, 0, static_cast<hipStream_t>(stream));
+        return check_launch(fn);
+    }
+    REQUIRE_PTR(fn, topk_idx);
+    REQUIRE_PTR(fn, row_of_assign);
+    REQUIRE_PTR(fn, assign_of_row);
+    if (x) {
+        REQUIRE_PTR(fn, x);
+        REQUIRE_PTR(fn, x_perm);
+    }
+    const size_t need = permute_workspace_bytes(T, K, E);
+    if (workspace == nullptr || workspace_bytes < need)
+        return fail(MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                    workspace ? workspace_bytes : (size_t)0);
+    REQUIRE_PTR(fn, workspace);
+    const int r_max = moe_max_rows(T, K, E, capacity);
+    launch_permute(x, topk_idx, T, H, E, K, capacity, r_max, dt, x_perm, expert_counts,
+                   expert_offsets, row_of_assign, assign_of_row, workspace,
+                   static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
+static moe_status_t expert_ffn(const char* fn, int phase, const void* x_perm,
+                               const int32_t* expert_offsets, int R_max, int H, int F, int E,
+                               const void* w_gate, const void* w_up, const void* w_down,
+                               moe_dtype_t dt, void* h, void* y_perm, moe_stream_t stream) {
+    if (dt != MOE_F32 && dt != MOE_BF16) return fail(MOE_ERR_INVALID_ARG, "%s: unknown dtype %d", fn, (int)dt);
+    if (R_max < 0 || H <= 0 || F <= 0 || E <= 0)
+        return fail(MOE_ERR_INVALID_ARG, "%s: need R_max >= 0 and H, F, E > 0", fn);
+    if (E > kMaxExperts) return fail(MOE_ERR_UNSUPPORTED, "%s: E=%d exceeds the limit %d", fn, E, kMaxExperts);
+    const int vec = (dt == MOE_BF16) ? 8 : 4;
+    if (H % vec || F % vec)
+        return fail(MOE_ERR_UNSUPPORTED, "%s: H=%d and F=%d must be multiples of %d", fn, H, F, vec);
+    if (R_max == 0) return MOE_OK;
+    REQUIRE_PTR(fn, expert_offsets);
+    REQUIRE_PTR(fn, h);
+    if (phase & 1) {
+        REQUIRE_PTR(fn, x_perm);
+        REQUIRE_PTR(fn, w_gate);
+        REQUIRE_PTR(fn, w_up);
+    }
+    if (phase & 2) {
+        REQUIRE_PTR(fn, w_down);
+        REQUIRE_PTR(fn, y_perm);
+    }
+    if (!launch_expert_ffn(x_perm, expert_offsets, R_max, H, F, E, w_gate, w_up, w_down, dt, h, y_perm,
+                           g_gemm_variant, phase, static_cast<hipStream_t>(stream)))
+        return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
+    return check_launch(fn);
+}
+
+moe_status_t moe_grouped_gemm_swiglu(const void* x_perm, const int32_t* expert_offsets, int R_max,
+                                     int H, int F, int E, const void* w_gate, const void* w_up,
+                                     const void* w_down, moe_dtype_t dt, void* h_workspace,
+                                     void* y_perm, moe_stream_t stream) {
+    return expert_ffn("moe_grouped_gemm_swiglu", 3, x_perm, expert_offsets, R_max, H, F, E, w_gate, w_up,
+                      w_down, dt, h_workspace, y_perm, stream);
+}
+
+moe_status_t moe_expert_gate_up(const void* x_perm, const int32_t* expert_offsets, int R_max, int H,
+                                int F, int E, const void* w_gate, const void* w_up, moe_dtype_t dt,
+                                void* h, moe_stream_t stream) {
+    return expert_ffn("moe_expert_gate_up", 1, x_perm, expert_offsets, R_max, H, F, E, w_gate, w_up,
+                      nullptr, dt, h, nullptr, stream);
+}
+
+moe_status_t moe_expert_down(const void* h, const int32_t* expert_offsets, int R_max, int H, int F,
+                             int E, const void* w_down, moe_dtype_t dt, void* y_perm,
+                             moe_stream_t stream) {
+    return expert_ffn("moe_expert_down", 2, nullptr, expert_offsets, R_max, H, F, E, nullptr, nullptr,
+                      w_down, dt, const_cast<void*>(h), y_perm, stream);
+}
+
+moe_status_t moe_unpermute_combine(const void* y_perm, const int32_t* row_of_assign,
+                                   const float* topk_gate, const void* addend, int T, int H,
+                                   int K, int R_max, moe_dtype_t dt, void* y, moe_stream_t stream) {
+    static const char* fn = "moe_unpermute_combine";
+    if (moe_status_t st = check_dims(fn, T, H, K, K, dt)) return st;  // E plays no part here
+    if (R_max < 0) return fail(MOE_ERR_INVALID_ARG, "%s: R_max=%d is negative", fn, R_max);
+    if (T == 0) return MOE_OK;
+    REQUIRE_PTR(fn, row_of_assign);
+    REQUIRE_PTR(fn, topk_gate);
+    REQUIRE_PTR(fn, y);
+    if (R_max > 0) REQUIRE_PTR(fn, y_perm);
+    if (addend && !aligned16(addend)) return fail(MOE_ERR_INVALID_ARG, "%s: addend is not 16-byte aligned", fn);
+    launch_combine(y_perm, row_of_assign, topk_gate, addend, T, H, K, R_max, dt, y,
+                   static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
+size_t moe_layer_workspace_bytes(int T, int H, int E, int K, int F, int Fs, int capacity,
+                                 moe_dtype_t dt) {
+    if (T < 0 || H <= 0 || E <= 0 || K <= 0 || F <= 0 || Fs < 0) return 0;
+    return layer_layout(T, H, E, K, F, Fs, capacity, dt).total;
+}
+
+moe_status_t moe_layer_workspace_layout(int T, int H, int E, int K, int F, int Fs, int capacity,
+                                        moe_dtype_t dt, size_t* byte_offsets, int n) {
+    if (byte_offsets == nullptr || n < 11) return fail(MOE_ERR_INVALID_ARG, "moe_layer_workspace_layout: need room for 11 offsets");
+    const LayerLayout L = layer_layout(T, H, E, K, F, Fs, capacity, dt);
+    const size_t v[11] = {L.logits, L.idx, L.gate, L.counts, L.offsets, L.roa, L.aor, L.x_perm, L.h, L.y_perm, L.s_y};
+    memcpy(byte_offsets, v, sizeof v);
+    return MOE_OK;
+}
+
+moe_status_t moe_layer_forward(const void* x, const void* w_router, const float* logit_bias,
+                               const void* w_gate, const void* w_up, const void* w_down,
+                               const void* ws_gate, const void* ws_up, const void* ws_down,
+                               int T, int H, int E, int K, int F, int Fs, int renormalize,
+                               int capacity, moe_dtype_t dt, void* y, void* workspace,
+                               size_t workspace_bytes, moe_stream_t stream) {
+    static const char* fn = "moe_layer_forward";
+    if (moe_status_t st = check_dims(fn, T, H, E, K, dt)) return st;
+    if (F <= 0 || Fs < 0) return fail(MOE_ERR_INVALID_ARG, "%s: need F > 0 and Fs >= 0", fn);
+    const bool shared = Fs > 0;
+    if (shared && !(ws_gate && ws_up && ws_down))
+        return fail(MOE_ERR_INVALID_ARG, "%s: Fs > 0 needs ws_gate, ws_up and ws_down", fn);
+    if (T == 0) return MOE_OK;
+    REQUIRE_PTR(fn, y);
+    const LayerLayout L = layer_layout(T, H, E, K, F, Fs, capacity, dt);
+    if (workspace == nullptr || workspace_bytes < L.total)
+        return fail(MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, L.total,
+                    workspace ? workspace_bytes : (size_t)0);
+    REQUIRE_PTR(fn, workspace);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    float* logits = reinterpret_cast<float*>(ws + L.logits);
+    int32_t* idx = reinterpret_cast<int32_t*>(ws + L.idx);
+    float* gate = reinterpret_cast<float*>(ws + L.gate);
+    int32_t* counts = reinterpret_cast<int32_t*>(ws + L.counts);
+    int32_t* offsets = reinterpret_cast<int32_t*>(ws + L.offsets);
+    int32_t* roa = reinterpret_cast<int32_t*>(ws + L.roa);
+    int32_t* aor = reinterpret_cast<int32_t*>(ws + L.aor);
+
+    moe_status_t st = moe_router_topk(x, w_router, logit_bias, logits, T, H, E, K, renormalize, dt,
+                                      idx, gate, stream);
+    if (st) return st;
+    st = moe_permute(x, idx, T, H, E, K, capacity, dt, ws + L.x_perm, counts, offsets, roa, aor,
+                     ws + L.perm_ws, permute_workspace_bytes(T, K, E), stream);
+    if (st) return st;
+    st = moe_grouped_gemm_swiglu(ws + L.x_perm, offsets, L.r_max, H, F, E, w_gate, w_up, w_down, dt,
+                                 ws + L.h, ws + L.y_perm, stream);
+    if (st) return st;
+    const void* addend = nullptr;
+    if (shared) {
+        // the shared expert sees every token: one "expert" owning rows [0, T)
+        int32_t* so = reinterpret_cast<int32_t*>(ws + L.s_offsets);
+        launch_fill_i32(so, 2, 0, T, static_cast<hipStream_t>(stream));
+        st = moe_grouped_gemm_swiglu(x, so, T, H, Fs, 1, ws_gate, ws_up, ws_down, dt, ws + L.s_h,
+                                     ws + L.s_y, stream);
+        if (st) return st;
+        addend = ws + L.s_y;
+    }
+    return moe_unpermute_combine(ws + L.y_perm, roa, gate, addend, T, H, K, L.r_max, dt, y, stream);
+}
+
+moe_status_t moe_set_option(const char* name, int value) {
+    if (name && strcmp(name, "gemm_variant") == 0) {
+        g_gemm_variant = value;
+        return MOE_OK;
+    }
+    return fail(MOE_ERR_INVALID_ARG, "moe_set_option: unknown option '%s'", name ? name : "(null)");
+}
+
+}  // extern "C"

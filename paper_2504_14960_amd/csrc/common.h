@@ -1,0 +1,64 @@
+// Shared declarations of the HIP side of the MoE hot path (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/moe.h"
+
+namespace moe {
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern in memory
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kWave = 64;
+constexpr int kMaxExperts = 256;
+constexpr int kMaxTopK = 64;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+    return __uint_as_float(static_cast<uint32_t>(v) << 16);
+}
+
+// round-to-nearest-even; gfx950 has a native conversion for it
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    __bf16 b = static_cast<__bf16>(f);
+    return __builtin_bit_cast(bf16_t, b);
+}
+
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+    return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+
+// host-side error reporting (api.hip)
+moe_status_t fail(moe_status_t st, const char* fmt, ...);
+moe_status_t check_launch(const char* what);
+
+// ---- kernel launchers (one per source file); all enqueue on `s` and return ----
+void launch_router(const void* x, const void* w, const float* bias, float* logits, int T, int H,
+                   int E, int K, int renorm, moe_dtype_t dt, int32_t* idx, float* gate,
+                   hipStream_t s);
+
+size_t permute_workspace_bytes(int T, int K, int E);
+void launch_permute(const void* x, const int32_t* idx, int T, int H, int E, int K, int capacity,
+                    int r_max, moe_dtype_t dt, void* x_perm, int32_t* counts, int32_t* offsets,
+                    int32_t* row_of_assign, int32_t* assign_of_row, void* ws, hipStream_t s);
+
+void launch_combine(const void* y_perm, const int32_t* row_of_assign, const float* gate,
+                    const void* addend, int T, int H, int K, int r_max, moe_dtype_t dt, void* y,
+                    hipStream_t s);
+
+// grouped NT GEMMs of the expert FFN.  phase bit 0: gate/up + SwiGLU (x_perm ->
+// h); bit 1: down projection (h -> y_perm).  Returns false if unsupported.
+bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                       const void* w_gate, const void* w_up, const void* w_down, moe_dtype_t dt,
+                       void* h, void* y_perm, int variant, int phase, hipStream_t s);
+
+void launch_fill_i32(int32_t* p, int n, int32_t v0, int32_t step, hipStream_t s);
+
+}  // namespace moe

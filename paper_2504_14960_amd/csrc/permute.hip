@@ -1,0 +1,214 @@
+// a2. Permute: the local part of the paper's token dispatching (Section 3.1.2:
+// rows of one expert contiguous in memory) with the capacity rule of Eq. 4 and
+// sub-sequence dropping (Section 3.3).
+//
+// The permutation is a stable counting sort of the T*K assignments by expert,
+// built without any slot-claiming atomics so the maps are bit-reproducible:
+//   1. permute_hist_kernel  per chunk of 1024 assignments, a per-expert
+//                           histogram (integer LDS atomics: only counts).
+//   2. permute_map_kernel   every workgroup sums the chunk histograms (totals
+//                           and its own exclusive base), scans the clamped
+//                           counts into offsets, ranks its chunk's assignments
+//                           with wave ballots and writes both maps.
+//   3. permute_copy_kernel  one wave per token: the row is read once with
+//                           16-byte lanes and stored to each kept destination.
+#include "common.h"
+
+namespace moe {
+
+namespace {
+
+constexpr int kChunk = 1024;  // assignments per workgroup
+constexpr int kUnits = kChunk / 64;
+
+__global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __restrict__ idx, int A,
+                                                           int E, int32_t* __restrict__ chunk_hist) {
+    __shared__ int hist[kMaxExperts];
+    for (int e = threadIdx.x; e < E; e += 256) hist[e] = 0;
+    __syncthreads();
+    const int a0 = blockIdx.x * kChunk;
+#pragma unroll
+    for (int j = 0; j < kChunk / 256; ++j) {
+        const int a = a0 + j * 256 + threadIdx.x;
+        if (a < A) {
+            const int e = idx[a];
+            if ((unsigned)e < (unsigned)E) atomicAdd(&hist[e], 1);
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 256) chunk_hist[(size_t)blockIdx.x * E + e] = hist[e];
+}
+
+__global__ __launch_bounds__(256) void permute_map_kernel(
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ chunk_hist, int A, int E,
+    int capacity, int r_max, int nchunks, int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ row_of_assign,
+    int32_t* __restrict__ assign_of_row) {
+    __shared__ int tot[kMaxExperts];
+    __shared__ int base[kMaxExperts];
+    __shared__ int scan[2][kMaxExperts];
+    __shared__ int off[kMaxExperts + 1];
+    __shared__ int unit_cnt[kUnits][kMaxExperts];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunk = blockIdx.x;
+
+    tot[tid] = 0;
+    base[tid] = 0;
+    for (int i = tid; i < kUnits * kMaxExperts; i += 256) (&unit_cnt[0][0])[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < nchunks * E; i += 256) {
+        const int c = i / E, e = i - c * E;
+        const int v = chunk_hist[i];
+        if (v) {
+            atomicAdd(&tot[e], v);
+            if (c < chunk) atomicAdd(&base[e], v);
+        }
+    }
+    __syncthreads();
+    // counts = min(total, capacity); offsets = exclusive scan (256-wide Hillis-Steele)
+    const int cnt = (tid < E) ? ((capacity > 0 && tot[tid] > capacity) ? capacity : tot[tid]) : 0;
+    scan[0][tid] = cnt;
+    __syncthreads();
+    int cur = 0;
+    for (int d = 1; d < kMaxExperts; d <<= 1) {
+        const int v = scan[cur][tid] + ((tid >= d) ? scan[cur][tid - d] : 0);
+        scan[cur ^ 1][tid] = v;
+        cur ^= 1;
+        __syncthreads();
+    }
+    const int incl = scan[cur][tid];
+    if (tid < E) off[tid + 1] = incl;
+    if (tid == 0) off[0] = 0;
+    if (chunk == 0) {
+        if (tid < E) {
+            counts[tid] = cnt;
+            offsets[tid + 1] = incl;
+        }
+        if (tid == 0) offsets[0] = 0;
+    }
+
+    // rank of every assignment of this chunk inside its (expert, 64-assignment unit)
+    int my_e[kChunk / 256], my_r[kChunk / 256];
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+    for (int j = 0; j < kChunk / 256; ++j) {
+        const int u = j * 4 + wave;
+        const int a = chunk * kChunk + u * 64 + lane;
+        int e = (a < A) ? idx[a] : -1;
+        const bool valid = (unsigned)e < (unsigned)E;
+        if (!valid) e = -1;
+        int r = 0;
+        uint64_t remaining = __ballot(valid);
+        while (remaining) {
+            const int leader = __ffsll((unsigned long long)remaining) - 1;
+            const int e0 = __shfl(e, leader, 64);
+            const uint64_t mask = __ballot(e == e0);
+            if (e == e0) r = __popcll(mask & lt_mask);
+            if (lane == leader) unit_cnt[u][e0] = __popcll(mask);
+            remaining &= ~mask;
+        }
+        my_e[j] = e;
+        my_r[j] = r;
+    }
+    __syncthreads();
+    if (tid < E) {
+        int run = 0;
+#pragma unroll
+        for (int u = 0; u < kUnits; ++u) {
+            const int c = unit_cnt[u][tid];
+            unit_cnt[u][tid] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kChunk / 256; ++j) {
+        const int u = j * 4 + wave;
+        const int a = chunk * kChunk + u * 64 + lane;
+        if (a < A) {
+            const int e = my_e[j];
+            int row = -1;
+            if (e >= 0) {
+                const int rank = base[e] + unit_cnt[u][e] + my_r[j];
+                if (capacity <= 0 || rank < capacity) row = off[e] + rank;
+            }
+            if (row >= r_max) row = -1;  // cannot happen for a consistent r_max; never an address
+            row_of_assign[a] = row;
+            if (row >= 0) assign_of_row[row] = a;
+        }
+    }
+    // rows past the kept total are marked unused
+    const int R = off[E];
+    for (int r = R + chunk * 256 + tid; r < r_max; r += nchunks * 256) assign_of_row[r] = -1;
+}
+
+// One wave per token.  row_bytes is a multiple of 16.
+__global__ __launch_bounds__(256) void permute_copy_kernel(const uint8_t* __restrict__ x,
+                                                           const int32_t* __restrict__ row_of_assign,
+                                                           uint8_t* __restrict__ x_perm, int T, int K,
+                                                           int row_bytes, int r_max) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int t = blockIdx.x * 4 + wave; t < T; t += gridDim.x * 4) {
+        int my_row = (lane < K) ? row_of_assign[(size_t)t * K + lane] : -1;
+        if ((unsigned)my_row >= (unsigned)r_max) my_row = -1;
+        const uint64_t kept = __ballot(my_row >= 0);
+        if (!kept) continue;
+        const uint8_t* src = x + (size_t)t * row_bytes;
+        for (int o0 = 0; o0 < row_bytes; o0 += 4096) {  // uniform trip count: shuffles inside
+            const int o = o0 + lane * 16;
+            u32x4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (o + i * 1024 < row_bytes)
+                    v[i] = *reinterpret_cast<const u32x4*>(src + o + i * 1024);
+            uint64_t m = kept;
+            while (m) {
+                const int k = __ffsll((unsigned long long)m) - 1;
+                m &= m - 1;
+                const int row = __shfl(my_row, k, 64);
+                uint8_t* dst = x_perm + (size_t)row * row_bytes + o;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (o + i * 1024 < row_bytes) *reinterpret_cast<u32x4*>(dst + i * 1024) = v[i];
+            }
+        }
+    }
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int n, int32_t v0, int32_t step) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v0 + i * step;
+}
+
+}  // namespace
+
+size_t permute_workspace_bytes(int T, int K, int E) {
+    const long long A = (long long)T * K;
+    const long long nchunks = (A + kChunk - 1) / kChunk;
+    return (size_t)((nchunks > 0 ? nchunks : 1) * E) * sizeof(int32_t);
+}
+
+void launch_permute(const void* x, const int32_t* idx, int T, int H, int E, int K, int capacity,
+                    int r_max, moe_dtype_t dt, void* x_perm, int32_t* counts, int32_t* offsets,
+                    int32_t* row_of_assign, int32_t* assign_of_row, void* ws, hipStream_t s) {
+    const int A = T * K;
+    const int nchunks = (A + kChunk - 1) / kChunk;
+    int32_t* chunk_hist = static_cast<int32_t*>(ws);
+    hipLaunchKernelGGL(permute_hist_kernel, dim3(nchunks), dim3(256), 0, s, idx, A, E, chunk_hist);
+    hipLaunchKernelGGL(permute_map_kernel, dim3(nchunks), dim3(256), 0, s, idx, chunk_hist, A, E,
+                       capacity, r_max, nchunks, counts, offsets, row_of_assign, assign_of_row);
+    if (x != nullptr && x_perm != nullptr) {
+        const int row_bytes = H * (dt == MOE_BF16 ? 2 : 4);
+        int grid = (T + 3) / 4;
+        if (grid > 256 * 16) grid = 256 * 16;
+        hipLaunchKernelGGL(permute_copy_kernel, dim3(grid), dim3(256), 0, s,
+                           static_cast<const uint8_t*>(x), row_of_assign,
+                           static_cast<uint8_t*>(x_perm), T, K, row_bytes, r_max);
+    }
+}
+
+void launch_fill_i32(int32_t* p, int n, int32_t v0, int32_t step, hipStream_t s) {
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((n + 63) / 64), dim3(64), 0, s, p, n, v0, step);
+}
+
+}  // namespace moe

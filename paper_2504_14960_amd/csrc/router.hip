@@ -1,0 +1,321 @@
+// a1. Router: logits = x W_g^T (+ bias), softmax over experts, top-K gating
+// (Eq. 2 and Eq. 3, Section 3.1.1; router paragraph of Section 3.3).
+//
+// bf16 path: one workgroup owns 16*MB tokens and all experts.  Its four waves
+// split the hidden dimension; each wave streams its slices of the token rows
+// with fully coalesced 16-byte loads, parks them in a wave-private LDS region
+// and re-reads them in MFMA operand order (16x16x32 bf16, fp32 accumulate).
+// The router weight is small and stays in L2; its fragments are read straight
+// from global memory.  Partial sums are folded in a fixed wave order, so the
+// logits are bit-reproducible.  Selection is done by groups of lanes, one
+// group per token, with butterfly reductions on (value desc, index asc) keys.
+#include "common.h"
+
+namespace moe {
+
+namespace {
+
+__device__ __forceinline__ bool ranks_before(float a, int ia, float b, int ib) {
+    return (a > b) || (a == b && ia < ib);
+}
+
+// One token per group of G lanes (G a power of two, <= 64); lane `lig` of the
+// group holds the logits of experts lig + j*G, j < VPL.  Lane k of the group
+// writes slot k.
+template <int VPL>
+__device__ __forceinline__ void select_topk(const float (&vin)[VPL], int lig, int G, int E, int K,
+                                            int renorm, bool valid, int32_t* idx_out,
+                                            float* gate_out) {
+    float v[VPL];
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+        const int e = lig + j * G;
+        float x = vin[j];
+        x = (x != x) ? -INFINITY : x;  // NaN ranks last
+        v[j] = (e < E) ? x : -INFINITY;
+        m = fmaxf(m, v[j]);
+    }
+    for (int off = G >> 1; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, G));
+    float z = 0.f;
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+        const int e = lig + j * G;
+        if (e < E) z += expf(v[j] - m);
+    }
+    for (int off = G >> 1; off > 0; off >>= 1) z += __shfl_xor(z, off, G);
+
+    uint32_t taken = 0;
+    float my_gate = 0.f, gsum = 0.f;
+    int my_idx = 0;
+    for (int k = 0; k < K; ++k) {
+        float bv = -INFINITY;
+        int be = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+            const int e = lig + j * G;
+            if (e < E && !((taken >> j) & 1u) && ranks_before(v[j], e, bv, be)) {
+                bv = v[j];
+                be = e;
+            }
+        }
+        for (int off = G >> 1; off > 0; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, G);
+            const int oe = __shfl_xor(be, off, G);
+            if (ranks_before(ov, oe, bv, be)) {
+                bv = ov;
+                be = oe;
+            }
+        }
+        if (be < E && (be & (G - 1)) == lig) taken |= 1u << (be / G);
+        const float p = expf(bv - m) / z;
+        gsum += p;
+        if (lig == k) {
+            my_gate = p;
+            my_idx = be;
+        }
+    }
+    if (renorm) my_gate /= gsum;
+    if (valid && lig < K) {
+        idx_out[lig] = my_idx;
+        gate_out[lig] = my_gate;
+    }
+}
+
+__host__ __device__ inline int group_lanes(int E) {
+    int g = 1;
+    while (g < E && g < 64) g <<= 1;
+    return g;
+}
+
+// Selection for `ntok` tokens whose logits sit in `rows` (row stride `ld`, LDS
+// or global), spread over the 4 waves of the workgroup.
+template <int VPL>
+__device__ __forceinline__ void select_block(const float* rows, int ld, int ntok, int t0, int T,
+                                             int E, int K, int renorm, int32_t* topk_idx,
+                                             float* topk_gate) {
+    const int G = group_lanes(E);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nwaves = blockDim.x >> 6;
+    const int per_wave = 64 / G;
+    const int lig = lane & (G - 1), grp = lane / G;
+    for (int base = wave * per_wave; base < ntok; base += nwaves * per_wave) {
+        const int lt = base + grp;
+        const bool valid = lt < ntok && (t0 + lt) < T;
+        float v[VPL];
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+            const int e = lig + j * G;
+            v[j] = (valid && e < E) ? rows[(size_t)lt * ld + e] : -INFINITY;
+        }
+        const size_t o = (size_t)(t0 + (valid ? lt : 0)) * K;
+        select_topk<VPL>(v, lig, G, E, K, renorm, valid, topk_idx + o, topk_gate + o);
+    }
+}
+
+__device__ __forceinline__ void select_dispatch(const float* rows, int ld, int ntok, int t0, int T,
+                                                int E, int K, int renorm, int32_t* topk_idx,
+                                                float* topk_gate) {
+    if (E <= 64)
+        select_block<1>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+    else if (E <= 128)
+        select_block<2>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+    else
+        select_block<4>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+}
+
+// ------------------------------------------------------------------ bf16 / MFMA
+template <int MB, int NB>
+__global__ __launch_bounds__(256) void router_bf16_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, const float* __restrict__ bias,
+    float* __restrict__ logits, int T, int H, int E, int K, int renorm,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate) {
+    constexpr int TOK = 16 * MB;      // tokens per workgroup
+    constexpr int LPR = 32 / MB;      // lanes covering one row slice
+    constexpr int KC = LPR * 8;       // hidden elements per slice
+    constexpr int KCP = KC + 8;       // padded LDS row (elements)
+    constexpr int RPI = 2 * MB;       // rows per load instruction
+    constexpr int EP = 16 * NB;       // experts padded to the MFMA N size
+    __shared__ __attribute__((aligned(16))) bf16_t xs[4][TOK][KCP];
+    __shared__ float red[TOK][EP + 1];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t0 = blockIdx.x * TOK;
+    const int nchunks = (H + KC - 1) / KC;
+
+    f32x4 acc[MB][NB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int lrow = lane / LPR, lcol = (lane % LPR) * 8;
+    u32x4 xr[8];
+    auto load_chunk = [&](int c) {
+        const int k = c * KC + lcol;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t = t0 + i * RPI + lrow;
+            u32x4 v = u32x4{0u, 0u, 0u, 0u};
+            if (t < T && k < H) v = *reinterpret_cast<const u32x4*>(x + (size_t)t * H + k);
+            xr[i] = v;
+        }
+    };
+
+    if (wave < nchunks) load_chunk(wave);
+    const int fr = lane & 15, fg = lane >> 4;  // fragment row / k-group
+    for (int c = wave; c < nchunks; c += 4) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<u32x4*>(&xs[wave][i * RPI + lrow][lcol]) = xr[i];
+        if (c + 4 < nchunks) load_chunk(c + 4);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int kc0 = c * KC;
+#pragma unroll
+        for (int s = 0; s < KC / 32; ++s) {
+            bf16x8 bfrag[NB];
+            const int k = kc0 + s * 32 + fg * 8;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int e = b * 16 + fr;
+                u32x4 v = u32x4{0u, 0u, 0u, 0u};
+                if (e < E && k < H) v = *reinterpret_cast<const u32x4*>(w + (size_t)e * H + k);
+                bfrag[b] = __builtin_bit_cast(bf16x8, v);
+            }
+#pragma unroll
+            for (int a = 0; a < MB; ++a) {
+                const u32x4 av = *reinterpret_cast<const u32x4*>(&xs[wave][a * 16 + fr][s * 32 + fg * 8]);
+                const bf16x8 afrag = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag[b], acc[a][b], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // fold the four partial sums in wave order 0,1,2,3 (fixed => reproducible)
+    for (int ww = 0; ww < 4; ++ww) {
+        if (wave == ww) {
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float* p = &red[a * 16 + fg * 4 + r][b * 16 + fr];
+                        *p = (ww == 0) ? acc[a][b][r] : (*p + acc[a][b][r]);
+                    }
+        }
+        __syncthreads();
+    }
+    // bias, write logits
+    for (int i = threadIdx.x; i < TOK * E; i += 256) {
+        const int lt = i / E, e = i - lt * E;
+        float v = red[lt][e];
+        if (bias) v += bias[e];
+        red[lt][e] = v;
+        if (t0 + lt < T) logits[(size_t)(t0 + lt) * E + e] = v;
+    }
+    __syncthreads();
+    select_dispatch(&red[0][0], EP + 1, TOK, t0, T, E, K, renorm, topk_idx, topk_gate);
+}
+
+// ------------------------------------------------------------------ fp32 / VALU
+// One wave per token; lanes stride the hidden dimension, one expert at a time.
+__global__ __launch_bounds__(256) void router_f32_kernel(
+    const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ bias,
+    float* __restrict__ logits, int T, int H, int E, int K, int renorm,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate) {
+    __shared__ float red[4][kMaxExperts];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t0 = blockIdx.x * 4;
+    const int t = t0 + wave;
+    if (t < T) {
+        const float* xr = x + (size_t)t * H;
+        for (int e = 0; e < E; ++e) {
+            const float* wr = w + (size_t)e * H;
+            float s = 0.f;
+            for (int h = lane * 4; h < H; h += 256) {
+                const f32x4 a = *reinterpret_cast<const f32x4*>(xr + h);
+                const f32x4 b = *reinterpret_cast<const f32x4*>(wr + h);
+                s = fmaf(a[0], b[0], s);
+                s = fmaf(a[1], b[1], s);
+                s = fmaf(a[2], b[2], s);
+                s = fmaf(a[3], b[3], s);
+            }
+            for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+            if (bias) s += bias[e];
+            if (lane == 0) {
+                red[wave][e] = s;
+                logits[(size_t)t * E + e] = s;
+            }
+        }
+    }
+    __syncthreads();
+    select_dispatch(&red[0][0], kMaxExperts, 4, t0, T, E, K, renorm, topk_idx, topk_gate);
+}
+
+// ------------------------------------------------------------------ selection only
+__global__ __launch_bounds__(256) void topk_only_kernel(const float* __restrict__ logits, int T,
+                                                        int E, int K, int renorm,
+                                                        int32_t* __restrict__ topk_idx,
+                                                        float* __restrict__ topk_gate) {
+    const int G = group_lanes(E);
+    const int per_block = 4 * (64 / G);
+    for (int t0 = blockIdx.x * per_block; t0 < T; t0 += gridDim.x * per_block)
+        select_dispatch(logits + (size_t)t0 * E, E, per_block, t0, T, E, K, renorm, topk_idx, topk_gate);
+}
+
+template <int MB, int NB>
+void launch_bf16(const void* x, const void* w, const float* bias, float* logits, int T, int H, int E,
+                 int K, int renorm, int32_t* idx, float* gate, hipStream_t s) {
+    const int grid = (T + 16 * MB - 1) / (16 * MB);
+    hipLaunchKernelGGL((router_bf16_kernel<MB, NB>), dim3(grid), dim3(256), 0, s,
+                       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), bias, logits, T,
+                       H, E, K, renorm, idx, gate);
+}
+
+}  // namespace
+
+void launch_router(const void* x, const void* w, const float* bias, float* logits, int T, int H,
+                   int E, int K, int renorm, moe_dtype_t dt, int32_t* idx, float* gate,
+                   hipStream_t s) {
+    if (x == nullptr) {
+        const int per_block = 4 * (64 / group_lanes(E));
+        int grid = (T + per_block - 1) / per_block;
+        if (grid > 4096) grid = 4096;
+        hipLaunchKernelGGL(topk_only_kernel, dim3(grid), dim3(256), 0, s, logits, T, E, K, renorm, idx, gate);
+        return;
+    }
+    if (dt == MOE_F32) {
+        hipLaunchKernelGGL(router_f32_kernel, dim3((T + 3) / 4), dim3(256), 0, s,
+                           static_cast<const float*>(x), static_cast<const float*>(w), bias, logits,
+                           T, H, E, K, renorm, idx, gate);
+        return;
+    }
+    const int nb = (E + 15) / 16;
+    // tokens per workgroup: enough workgroups to fill 256 CUs, but for many
+    // experts a taller tile so the router weight is re-read less often
+    int mb = (T >= 32768) ? 4 : (T >= 16384 ? 2 : 1);
+    if (nb >= 4 && mb < 2) mb = 2;
+#define ROUTER_CASE(M, N)                                                          \
+    launch_bf16<M, N>(x, w, bias, logits, T, H, E, K, renorm, idx, gate, s);       \
+    return;
+    if (nb <= 1) {
+        if (mb == 4) { ROUTER_CASE(4, 1) } else if (mb == 2) { ROUTER_CASE(2, 1) } else { ROUTER_CASE(1, 1) }
+    } else if (nb <= 2) {
+        if (mb == 4) { ROUTER_CASE(4, 2) } else if (mb == 2) { ROUTER_CASE(2, 2) } else { ROUTER_CASE(1, 2) }
+    } else if (nb <= 4) {
+        if (mb == 4) { ROUTER_CASE(4, 4) } else { ROUTER_CASE(2, 4) }
+    } else if (nb <= 8) {
+        ROUTER_CASE(2, 8)
+    } else {
+        ROUTER_CASE(1, 16)
+    }
+#undef ROUTER_CASE
+}
+
+}  // namespace moe

@@ -1,0 +1,105 @@
+"""a3 on the GPU against the oracle: grouped SwiGLU expert FFN over ragged rows."""
+import numpy as np
+import pytest
+
+import oracle
+from moe_inputs import get_config, make_layer_inputs, make_tokens
+from helpers import assert_close, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+ALL_VARIANTS = [1, 2, 3, 4, 5, 6, 7, 8, 11, 12, 13, 14, 15, 99]
+
+
+def _offsets(counts):
+    return np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+
+
+def _run(x_perm, offsets, inp, variant, r_max=None):
+    import torch
+    import paper_2504_14960_amd as moe
+    R = int(offsets[-1])
+    r_max = R if r_max is None else r_max
+    E, F, H = inp["w_gate"].shape
+    dx = to_dev(x_perm)
+    h = torch.zeros((r_max, F), dtype=dx.dtype, device="cuda")
+    y = torch.zeros((r_max, H), dtype=dx.dtype, device="cuda")
+    moe.set_option("gemm_variant", variant)
+    try:
+        moe.grouped_gemm_swiglu(dx, to_dev(offsets), to_dev(inp["w_gate"]), to_dev(inp["w_up"]),
+                                to_dev(inp["w_down"]), h, y)
+        torch.cuda.synchronize()
+    finally:
+        moe.set_option("gemm_variant", 0)
+    return to_host(h), to_host(y)
+
+
+def _case(H, F, E, counts, bf16=True, seed=4000, r_pad=0):
+    cfg = get_config("mixtral8x7b").scaled(T=8, H=H, E=E, K=1, F=F, seed=seed, dtype="bf16" if bf16 else "f32")
+    inp = make_layer_inputs(cfg, ["w_gate", "w_up", "w_down"])
+    offsets = _offsets(counts)
+    R = int(offsets[-1])
+    x_perm = make_tokens(seed + 1, R + r_pad, H, bf16=bf16)
+    y_ref, h_ref = oracle.experts(x_perm, offsets, inp["w_gate"], inp["w_up"], inp["w_down"], want_h=True)
+    return inp, x_perm, offsets, h_ref, y_ref
+
+
+@pytest.fixture(scope="module")
+def ragged_case():
+    # spans several 256-row tiles, ragged tails, an empty expert, a 1-row expert
+    return _case(H=256, F=384, E=6, counts=[700, 0, 1, 300, 513, 86])
+
+
+@pytest.mark.parametrize("variant", ALL_VARIANTS)
+def test_every_kernel_variant_on_ragged_experts(ragged_case, variant):
+    inp, x_perm, offsets, h_ref, y_ref = ragged_case
+    h, y = _run(x_perm, offsets, inp, variant)
+    assert_close(h, h_ref, True, f"h (variant {variant})")
+    assert_close(y, y_ref, True, f"y_perm (variant {variant})")
+
+
+@pytest.mark.parametrize("variant", [0, 11, 12])
+def test_deep_contraction_and_fine_grained_experts(variant):
+    # long K loops (many k-tiles) and many small experts
+    inp, x_perm, offsets, h_ref, y_ref = _case(H=1536, F=128, E=3, counts=[130, 257, 40], seed=4100)
+    h, y = _run(x_perm, offsets, inp, variant)
+    assert_close(h, h_ref, True, "h deep")
+    assert_close(y, y_ref, True, "y deep")
+    rng = np.random.default_rng(7)
+    counts = rng.integers(0, 90, size=64).tolist()
+    inp, x_perm, offsets, h_ref, y_ref = _case(H=128, F=192, E=64, counts=counts, seed=4200)
+    h, y = _run(x_perm, offsets, inp, variant)
+    assert_close(h, h_ref, True, "h fine-grained")
+    assert_close(y, y_ref, True, "y fine-grained")
+
+
+def test_rows_past_the_last_expert_are_untouched_and_result_is_reproducible():
+    inp, x_perm, offsets, h_ref, y_ref = _case(H=128, F=256, E=4, counts=[100, 50, 0, 270], seed=4300, r_pad=37)
+    R = int(offsets[-1])
+    h1, y1 = _run(x_perm, offsets, inp, 0, r_max=R + 37)
+    h2, y2 = _run(x_perm, offsets, inp, 0, r_max=R + 37)
+    assert (y1[R:] == 0).all() and (h1[R:] == 0).all()
+    np.testing.assert_array_equal(y1, y2)
+    np.testing.assert_array_equal(h1, h2)
+    assert_close(y1[:R], y_ref, True, "y_perm")
+
+
+def test_shapes_outside_the_mfma_fast_path_use_the_plain_kernel():
+    inp, x_perm, offsets, h_ref, y_ref = _case(H=72, F=40, E=3, counts=[65, 3, 130], seed=4400)
+    h, y = _run(x_perm, offsets, inp, 0)
+    assert_close(h, h_ref, True, "h odd shape")
+    assert_close(y, y_ref, True, "y odd shape")
+
+
+def test_fp32_experts():
+    inp, x_perm, offsets, h_ref, y_ref = _case(H=128, F=256, E=8, counts=[64, 70, 1, 0, 129, 33, 90, 125],
+                                               bf16=False, seed=4500)
+    h, y = _run(x_perm, offsets, inp, 0)
+    assert_close(h, h_ref, False, "h fp32")
+    assert_close(y, y_ref, False, "y fp32")
+
+
+def test_all_experts_empty_is_a_no_op():
+    inp, x_perm, offsets, h_ref, y_ref = _case(H=128, F=128, E=4, counts=[0, 0, 0, 0], seed=4600, r_pad=16)
+    h, y = _run(x_perm, offsets, inp, 0, r_max=16)
+    assert (y == 0).all() and (h == 0).all()
