@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer forward hot path on one MI355X.
+
+A "step" is one pass of the whole path (router -> permute -> grouped SwiGLU
+expert GEMMs -> un-permute/combine, plus the shared expert where the workload
+has one) over one batch of seeded synthetic tokens that already sit in HBM.
+Default workload: the Mixtral-8x22B-shaped layer (T=8192, H=6144, E=8, K=2,
+F=16384, bf16, dropless, skewed router).
+
+Prints ONE JSON line: whole-path tokens/s (`value`), the roofline figures of
+the dominant kernel (the gate/up grouped GEMM) measured with HIP events on the
+launch stream inside the timed region, per-stage figures (`stages`) and the CPU
+oracle timed on a bounded sample of the same workload (`cpu_baseline`).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+NSETS = 4                   # rotating activation/workspace sets (defeats the 256 MB Infinity Cache)
+
+# HBM traffic of one gate/up GEMM launch at the default workload, from the
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (bytes);
+# None for workloads that were not profiled.
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="mixtral8x22b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
+    return ap.parse_args()
+
+
+def cpu_baseline(inp, capacity, target_s):
+    """Time the CPU oracle (as it stands) on the first S tokens of the batch."""
+    import numpy as np
+    import oracle
+    cfg = inp.cfg
+    t = inp.tensors
+
+    def run(S):
+        x = np.ascontiguousarray(t["x"][:S])
+        t0 = time.perf_counter()
+        oracle.layer_forward(x, t["w_router"], inp.bias, t["w_gate"], t["w_up"], t["w_down"], K=cfg.K,
+                             renormalize=cfg.renormalize, capacity_rows=capacity,
+                             ws_gate=t.get("ws_gate"), ws_up=t.get("ws_up"), ws_down=t.get("ws_down"))
+        return time.perf_counter() - t0
+
+    S = 8
+    dt = run(S)
+    S2 = int(max(S, min(cfg.T, S * target_s / max(dt, 1e-3))))
+    if S2 > 2 * S:
+        S, dt = S2, run(S2)
+    return {"value": S / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {S} tokens of the batch through oracle.layer_forward with the full weights, {dt:.1f} s"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all experts local, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2504_14960_amd as moe
+    from moe_inputs import get_config, make_layer_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    cfg = get_config(args.config)
+    T, H, E, K, F, Fs = cfg.T, cfg.H, cfg.E, cfg.K, cfg.F, cfg.shared_F
+    bf16 = cfg.dtype == "bf16"
+    es = 2 if bf16 else 4
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    capacity = moe.capacity_from_factor(cfg.capacity_factor, T, K, E) if cfg.capacity_factor else 0
+    r_max = moe.max_rows(T, K, E, capacity)
+
+    t_gen = time.perf_counter()
+    inp = make_layer_inputs(cfg)
+    t_gen = time.perf_counter() - t_gen
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    w = {k: dev(v) for k, v in inp.tensors.items() if k != "x"}
+    bias = None if inp.bias is None else dev(inp.bias)
+    x_host = inp.tensors["x"]
+    sets = []
+    for i in range(NSETS):
+        xs = dev(np.roll(x_host, i * 17, axis=0)) if i else dev(x_host)
+        s = dict(
+            x=xs,
+            logits=torch.empty((T, E), dtype=torch.float32, device="cuda"),
+            idx=torch.empty((T, K), dtype=torch.int32, device="cuda"),
+            gate=torch.empty((T, K), dtype=torch.float32, device="cuda"),
+            counts=torch.empty((E,), dtype=torch.int32, device="cuda"),
+            offsets=torch.empty((E + 1,), dtype=torch.int32, device="cuda"),
+            roa=torch.empty((T * K,), dtype=torch.int32, device="cuda"),
+            aor=torch.empty((r_max,), dtype=torch.int32, device="cuda"),
+            pws=torch.empty((moe.permute_workspace_bytes(T, K, E) + 256,), dtype=torch.uint8, device="cuda"),
+            x_perm=torch.empty((r_max, H), dtype=tdt, device="cuda"),
+            h=torch.empty((r_max, F), dtype=tdt, device="cuda"),
+            y_perm=torch.empty((r_max, H), dtype=tdt, device="cuda"),
+            y=torch.empty((T, H), dtype=tdt, device="cuda"),
+        )
+        if Fs:
+            s["s_off"] = torch.tensor([0, T], dtype=torch.int32, device="cuda")
+            s["s_h"] = torch.empty((T, Fs), dtype=tdt, device="cuda")
+            s["s_y"] = torch.empty((T, H), dtype=tdt, device="cuda")
+        sets.append(s)
+
+    stage_names = ["router", "permute", "gate_up", "down"] + (["shared"] if Fs else []) + ["combine"]
+
+    def step(s, events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        moe.router_topk(s["x"], w["w_router"], bias, s["logits"], K, cfg.renormalize, s["idx"], s["gate"])
+        mark(1)
+        moe.permute(s["x"], s["idx"], E, capacity, s["x_perm"], s["counts"], s["offsets"], s["roa"], s["aor"], s["pws"])
+        mark(2)
+        moe.expert_gate_up(s["x_perm"], s["offsets"], w["w_gate"], w["w_up"], s["h"])
+        mark(3)
+        moe.expert_down(s["h"], s["offsets"], w["w_down"], s["y_perm"])
+        mark(4)
+        n = 4
+        addend = None
+        if Fs:
+            moe.grouped_gemm_swiglu(s["x"], s["s_off"], w["ws_gate"].unsqueeze(0), w["ws_up"].unsqueeze(0),
+                                    w["ws_down"].unsqueeze(0), s["s_h"], s["s_y"])
+            addend = s["s_y"]
+            n += 1
+            mark(n)
+        moe.unpermute_combine(s["y_perm"], s["roa"], s["gate"], addend, s["y"])
+        mark(n + 1)
+
+    for i in range(args.warmup):
+        step(sets[i % NSETS])
+    torch.cuda.synchronize()
+    R = int(sets[0]["offsets"][E].item())          # kept rows (outside the timed region)
+    counts = sets[0]["counts"].cpu().tolist()
+
+    nev = len(stage_names) + 1
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(nev)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(sets[i % NSETS], evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    stage_ms = {nm: sum(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(args.steps)) / args.steps
+                for j, nm in enumerate(stage_names)}
+
+    # algorithmic work (useful bytes / flops only)
+    maps = 8 * T * K
+    alg = {
+        "router": ("GB/s", T * H * es + T * (4 * E + 8 * K)),
+        "permute": ("GB/s", (T + R) * H * es + maps),
+        "gate_up": ("TFLOP/s", 4.0 * R * H * F),
+        "down": ("TFLOP/s", 2.0 * R * H * F),
+        "combine": ("GB/s", (R + T + (T if Fs else 0)) * H * es + maps),
+    }
+    if Fs:
+        alg["shared"] = ("TFLOP/s", 6.0 * T * H * Fs)
+    stages = {}
+    for nm in stage_names:
+        unit, work = alg[nm]
+        ms = stage_ms[nm]
+        rate = work / (ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
+        peak = PEAK_BF16_TFLOPS if unit == "TFLOP/s" else PEAK_HBM_GBS
+        stages[nm] = {"ms": round(ms, 4), "achieved": round(rate, 1), "unit": unit, "frac": round(rate / peak, 4)}
+
+    dom = stages["gate_up"]
+    roofline = {"kernel": "gate/up grouped GEMM (moe_expert_gate_up)", "bound": "mfma", "achieved": dom["achieved"],
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom["frac"],
+                "traffic": MEASURED_TRAFFIC.get(cfg.name)}
+
+    out = {
+        "metric": "MoE layer fwd tokens/s; grouped-GEMM % bf16 MFMA peak; permute GB/s % HBM",
+        "value": round(T / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name} layer: T={T} H={H} E={E} K={K} F={F}"
+                               + (f" shared_F={Fs}" if Fs else "")
+                               + (f" capacity={capacity}" if capacity else " dropless")
+                               + (f" bias={cfg.bias}" if cfg.bias else ""),
+                   "kept_rows": R, "rows_per_expert_min_max": [min(counts), max(counts)],
+                   "buffer_sets": NSETS, "input_generation_s": round(t_gen, 1)},
+        "roofline": roofline,
+        "stages": stages,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, capacity, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

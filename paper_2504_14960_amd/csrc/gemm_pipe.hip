@@ -39,7 +39,7 @@ __device__ __forceinline__ void pin_schedule() {
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, bool EARLY, int DBG = 0>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, int ntn) {
@@ -69,14 +69,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe_kernel(
     const Tile tile = find_tile<BM>(offsets, E, ntn, sched);
     if (!tile.valid) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, keep it scalar
     const int wm = wave / WGN, wn = wave % WGN;
     const int n0 = tile.ntile * OUTN;
+    constexpr bool PF = (DBG == 3);
+    constexpr int NPF = PF ? (BM + BN) / NT : 0;  // L2 prefetch touches per thread per k-tile
+    __shared__ uint32_t pf_sink[PF ? NT : 1];
 
     // ---- fetch slots: uniform bases + per-lane 32-bit byte offsets ----
     const int frow = tid / CPR, fchunk = tid % CPR;
-    const uint8_t* a_base = reinterpret_cast<const uint8_t*>(A + (size_t)tile.row0 * K);
-    const size_t b_row0 = ((size_t)tile.expert * N + n0) * K;
+    const uint8_t* a_base = reinterpret_cast<const uint8_t*>(A + (size_t)(DBG == 2 ? 0 : tile.row0) * K);
+    const size_t b_row0 = (DBG == 2) ? 0 : ((size_t)tile.expert * N + n0) * K;
     const uint8_t* b_base0 = reinterpret_cast<const uint8_t*>(B0 + b_row0);
     const uint8_t* b_base1 = SWIGLU ? reinterpret_cast<const uint8_t*>(B1 + b_row0) : b_base0;
     uint32_t a_goff[PA], b_goff[PB];
@@ -95,8 +99,36 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe_kernel(
     }
     const int wbase = (wave * 64 / CPR) * ROWB;  // this wave's 1 KiB slice of a fetch pass
 
+    // L2 prefetch: two k-tiles ahead, every thread touches one 128-byte line of
+    // "its" tile row(s) with a 4-byte direct load into a sink; nobody waits for it
+    const uint8_t* pf_ptr[NPF > 0 ? NPF : 1];
+    if (PF) {
+#pragma unroll
+        for (int q = 0; q < NPF; ++q) {
+            const int r = q * NT + tid;  // 0..BM-1: A rows, BM..BM+BN-1: B rows
+            if (r < BM) {
+                pf_ptr[q] = a_base + (size_t)min(r, tile.rows - 1) * K * 2;
+            } else {
+                const int rb = r - BM;
+                int f = SWIGLU ? (rb % (BN / 2)) : rb;
+                f = min(f, N - 1 - n0);
+                pf_ptr[q] = ((SWIGLU && rb >= BN / 2) ? b_base1 : b_base0) + (size_t)f * K * 2;
+            }
+        }
+    }
+    auto prefetch = [&](int kt_target) {
+        if (PF) {
+#pragma unroll
+            for (int q = 0; q < NPF; ++q)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(pf_ptr[q] + (size_t)kt_target * (BK * 2)),
+                    (__attribute__((address_space(3))) void*)(pf_sink + wave * 64), 4, 0, 0);
+        }
+    };
+
     auto fetch_one = [&](int i, int kbyte, uint8_t* st) {
         // i-th direct load of a k-tile: A passes first, then B passes
+        if (DBG == 1 && kbyte != 0) return;
         if (i < PA) {
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void*)(a_base + kbyte + a_goff[i]),
@@ -167,10 +199,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe_kernel(
     __syncthreads();
     read_frags(smem, 0, 0);
 
-    constexpr int L0 = (NLOAD + 2) / 3;           // loads issued under k-step 0
-    constexpr int L1 = (NLOAD - L0 + 1) / 2;      // under k-step 1
-    constexpr int L2 = NLOAD - L0 - L1;           // under k-step 2
-    static_assert(L0 <= NREAD && L1 <= NREAD && L2 <= NREAD, "more loads than interleave slots");
+    // EARLY: all of the next tile's loads go out under k-step 0 (longest flight
+    // time); else they are spread over k-steps 0..2
+    constexpr int L0 = EARLY ? NLOAD : (NLOAD + 2) / 3;   // loads issued under k-step 0
+    constexpr int L1 = EARLY ? 0 : (NLOAD - L0 + 1) / 2;  // under k-step 1
+    constexpr int L2 = NLOAD - L0 - L1;                   // under k-step 2
 
     for (int kt = 0; kt < KT - 1; ++kt) {
         const uint8_t* cur = smem + (kt & 1) * STAGE;
@@ -180,9 +213,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe_kernel(
         // k-step 0
 #pragma unroll
         for (int i = 0; i < L0; ++i) fetch_one(i, kbyte, nxt);
+        if (EARLY) prefetch(min(kt + 2, KT - 1));
         read_frags(cur, 1, 1);
         mfma_step(0);
-        pin_schedule<0, NREAD, NREAD, L0, NMFMA, MPR>();
+        pin_schedule<0, (L0 + (EARLY ? NPF : 0) > NREAD ? L0 + (EARLY ? NPF : 0) : NREAD), NREAD, L0 + (EARLY ? NPF : 0), NMFMA, MPR>();
         __builtin_amdgcn_sched_barrier(0);
         // k-step 1
 #pragma unroll
@@ -200,7 +234,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe_kernel(
         __builtin_amdgcn_sched_barrier(0);
         // next tile landed (this thread's part), this wave's reads of `cur` are
         // in registers: after the barrier `cur` may be overwritten and `nxt` read
-        __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0), lgkmcnt(0)
+        // lgkmcnt(0), expcnt(0) and vmcnt(NPF): the NPF youngest loads are this
+        // iteration's L2 prefetches, which may stay in flight
+        __builtin_amdgcn_s_waitcnt((NPF & 0xF) | ((NPF >> 4) << 14));
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         // k-step 3, first fragments of the next tile underneath
@@ -229,16 +265,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe_kernel(
         __builtin_amdgcn_sched_barrier(0);
     }
 
+    if (PF) wait_vmcnt0();
     store_tile<FM, FN, WM, WN, BN, SWIGLU>(acc, tile, C, N, n0, wm, wn, lane);
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, bool EARLY, int DBG = 0>
 void launch_pipe(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B0,
                  const void* B1, void* C, hipStream_t s) {
     constexpr int OUTN = SWIGLU ? BN / 2 : BN;
     constexpr size_t smem = 2 * (size_t)(BM + BN) * 64 * 2;
     const int ntn = (N + OUTN - 1) / OUTN;
-    auto kern = gemm_bf16_pipe_kernel<BM, BN, WGM, WGN, SWIGLU>;
+    auto kern = gemm_bf16_pipe_kernel<BM, BN, WGM, WGN, SWIGLU, EARLY, DBG>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -251,12 +288,12 @@ void launch_pipe(const void* A, const int32_t* offsets, int r_max, int E, int N,
                        static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C), ntn);
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, bool EARLY, int DBG = 0>
 void run_pipe_pair(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                    const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm,
                    int phase, hipStream_t s) {
-    if (phase & 1) launch_pipe<BM, BN, WGM, WGN, true>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, s);
-    if (phase & 2) launch_pipe<BM, BN, WGM, WGN, false>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
+    if (phase & 1) launch_pipe<BM, BN, WGM, WGN, true, EARLY, DBG>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, s);
+    if (phase & 2) launch_pipe<BM, BN, WGM, WGN, false, EARLY, DBG>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
 }
 
 }  // namespace
@@ -265,11 +302,19 @@ bool launch_pipe_ffn(const void* x_perm, const int32_t* offsets, int r_max, int 
                      const void* w_gate, const void* w_up, const void* w_down, void* h,
                      void* y_perm, int variant, int phase, hipStream_t s) {
     switch (variant) {
-        case 11: run_pipe_pair<256, 256, 2, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
-        case 12: run_pipe_pair<256, 256, 2, 4>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
-        case 13: run_pipe_pair<128, 256, 2, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
-        case 14: run_pipe_pair<256, 128, 2, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
-        case 15: run_pipe_pair<128, 128, 2, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 11: run_pipe_pair<256, 256, 2, 2, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 12: run_pipe_pair<256, 256, 2, 4, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 13: run_pipe_pair<128, 256, 2, 2, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 14: run_pipe_pair<256, 128, 2, 2, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 15: run_pipe_pair<128, 128, 2, 2, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 16: run_pipe_pair<256, 256, 2, 2, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 17: run_pipe_pair<256, 256, 2, 4, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 18: run_pipe_pair<256, 256, 2, 2, true, 3>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 19: run_pipe_pair<256, 256, 2, 4, true, 3>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 91: run_pipe_pair<256, 256, 2, 2, true, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 92: run_pipe_pair<256, 256, 2, 2, true, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 93: run_pipe_pair<256, 256, 2, 4, true, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 94: run_pipe_pair<256, 256, 2, 4, true, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         default: return false;
     }
 }

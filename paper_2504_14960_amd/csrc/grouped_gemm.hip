@@ -352,6 +352,14 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
         if (phase & 2) launch_simple_gemm<bf16_t, false>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
         return true;
     }
+    if (variant == 0) {
+        // tuned defaults (Mixtral-8x22B layer shape on MI355X): the 8-wave pipelined
+        // kernel for the gate/up GEMM, the 4-wave one for the down projection
+        bool ok = true;
+        if (phase & 1) ok = ok && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 17, 1, s);
+        if (phase & 2) ok = ok && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 16, 2, s);
+        return ok;
+    }
     if (variant >= 10 && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, variant, phase, s))
         return true;
     switch (variant) {
@@ -363,6 +371,7 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
         case 5: run_pair<128, 256, 64, 2, 2, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
         case 6: run_pair<128, 256, 64, 2, 2, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
         case 7: run_pair<128, 128, 64, 2, 2, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
+        case 9: run_pair<256, 256, 32, 2, 2, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
         case 8: run_pair<128, 128, 64, 2, 2, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
     }
     return true;
