@@ -356,8 +356,8 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
         // tuned defaults (Mixtral-8x22B layer shape on MI355X): the 8-wave pipelined
         // kernel for the gate/up GEMM, the 4-wave one for the down projection
         bool ok = true;
-        if (phase & 1) ok = ok && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 17, 1, s);
-        if (phase & 2) ok = ok && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 16, 2, s);
+        if (phase & 1) ok = ok && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 21, 1, s);
+        if (phase & 2) ok = ok && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 20, 2, s);
         return ok;
     }
     if (variant >= 10 && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, variant, phase, s))
