@@ -30,7 +30,7 @@ NSETS = 4                   # rotating activation/workspace sets (defeats the 25
 # HBM traffic of one gate/up GEMM launch at the default workload, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (bytes);
 # None for workloads that were not profiled.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {"mixtral8x22b": 11.30e9}   # 10.66 GB fetched + 0.64 GB written
 
 
 def parse_args():
@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--config", default="mixtral8x22b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy 5 times (scale reference for rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     return ap.parse_args()
 
 
@@ -83,6 +86,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
+    if args.copy_calibration:
+        src = torch.full((1 << 30,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30, "launches": 5}))
+        return
     cfg = get_config(args.config)
     T, H, E, K, F, Fs = cfg.T, cfg.H, cfg.E, cfg.K, cfg.F, cfg.shared_F
     bf16 = cfg.dtype == "bf16"
