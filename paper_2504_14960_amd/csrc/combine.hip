@@ -92,24 +92,127 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint8_t* __restrict_
     }
 }
 
+// Fast path for K <= KMAX (2, 4 or 8): all row indices and gates of a token are
+// made wave-uniform first, then every 16-byte slice of all K rows is requested
+// before the first FMA, so up to 8 loads per lane are in flight.  Whether an
+// assignment was dropped is wave-uniform, so skipping it costs a scalar branch
+// only; the sum still runs in ascending k.
+template <bool BF16, int KMAX>
+__global__ __launch_bounds__(256) void combine_small_k_kernel(
+    const uint8_t* __restrict__ y_perm, const int32_t* __restrict__ row_of_assign,
+    const float* __restrict__ gate, const uint8_t* __restrict__ addend, uint8_t* __restrict__ y, int T,
+    int K, int row_bytes, int r_max) {
+    constexpr int NV = BF16 ? 8 : 4;
+    constexpr int CP = 8 / KMAX;  // 1 KiB slices per pass
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int t = blockIdx.x * 4 + wave; t < T; t += gridDim.x * 4) {
+        int my_row = -1;
+        float my_gate = 0.f;
+        if (lane < K) {
+            my_row = row_of_assign[(size_t)t * K + lane];
+            my_gate = gate[(size_t)t * K + lane];
+        }
+        if ((unsigned)my_row >= (unsigned)r_max) my_row = -1;
+        int rows[KMAX];
+        float gates[KMAX];
+        bool keep[KMAX];
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const int r = __builtin_amdgcn_readlane(my_row, k);
+            keep[k] = r >= 0;
+            rows[k] = keep[k] ? r : 0;
+            gates[k] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_gate), k));
+        }
+        for (int o0 = 0; o0 < row_bytes; o0 += CP * 1024) {
+            u32x4 v[KMAX][CP];
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                const uint8_t* src = y_perm + (size_t)rows[k] * row_bytes;
+#pragma unroll
+                for (int i = 0; i < CP; ++i) {
+                    const int o = o0 + i * 1024 + lane * 16;
+                    v[k][i] = u32x4{0u, 0u, 0u, 0u};
+                    if (keep[k] && o < row_bytes) v[k][i] = *reinterpret_cast<const u32x4*>(src + o);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < CP; ++i) {
+                const int o = o0 + i * 1024 + lane * 16;
+                if (o >= row_bytes) continue;
+                float acc[NV];
+#pragma unroll
+                for (int j = 0; j < NV; ++j) acc[j] = 0.f;
+#pragma unroll
+                for (int k = 0; k < KMAX; ++k) {
+                    if (!keep[k]) continue;  // wave-uniform
+                    const float g = gates[k];
+                    if (BF16) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            acc[2 * j] = fmaf(g, __uint_as_float(v[k][i][j] << 16), acc[2 * j]);
+                            acc[2 * j + 1] = fmaf(g, __uint_as_float(v[k][i][j] & 0xffff0000u), acc[2 * j + 1]);
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[j] = fmaf(g, __uint_as_float(v[k][i][j]), acc[j]);
+                    }
+                }
+                const size_t at = (size_t)t * row_bytes + o;
+                if (addend) {
+                    const u32x4 av = *reinterpret_cast<const u32x4*>(addend + at);
+                    if (BF16) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            acc[2 * j] += __uint_as_float(av[j] << 16);
+                            acc[2 * j + 1] += __uint_as_float(av[j] & 0xffff0000u);
+                        }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[j] += __uint_as_float(av[j]);
+                    }
+                }
+                u32x4 out;
+                if (BF16) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) out[j] = pack2_bf16(acc[2 * j], acc[2 * j + 1]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) out[j] = __float_as_uint(acc[j]);
+                }
+                *reinterpret_cast<u32x4*>(y + at) = out;
+            }
+        }
+    }
+}
+
+template <bool BF16>
+void launch_combine_t(const void* y_perm, const int32_t* row_of_assign, const float* gate,
+                      const void* addend, int T, int H, int K, int r_max, void* y, hipStream_t s) {
+    int grid = (T + 3) / 4;
+    if (grid > 256 * 16) grid = 256 * 16;
+    const int row_bytes = H * (BF16 ? 2 : 4);
+    const uint8_t* yp = static_cast<const uint8_t*>(y_perm);
+    const uint8_t* ad = static_cast<const uint8_t*>(addend);
+    uint8_t* out = static_cast<uint8_t*>(y);
+    if (K <= 2)
+        hipLaunchKernelGGL((combine_small_k_kernel<BF16, 2>), dim3(grid), dim3(256), 0, s, yp, row_of_assign, gate, ad, out, T, K, row_bytes, r_max);
+    else if (K <= 4)
+        hipLaunchKernelGGL((combine_small_k_kernel<BF16, 4>), dim3(grid), dim3(256), 0, s, yp, row_of_assign, gate, ad, out, T, K, row_bytes, r_max);
+    else if (K <= 8)
+        hipLaunchKernelGGL((combine_small_k_kernel<BF16, 8>), dim3(grid), dim3(256), 0, s, yp, row_of_assign, gate, ad, out, T, K, row_bytes, r_max);
+    else
+        hipLaunchKernelGGL((combine_kernel<BF16>), dim3(grid), dim3(256), 0, s, yp, row_of_assign, gate, ad, out, T, K, row_bytes, r_max);
+}
+
 }  // namespace
 
 void launch_combine(const void* y_perm, const int32_t* row_of_assign, const float* gate,
                     const void* addend, int T, int H, int K, int r_max, moe_dtype_t dt, void* y,
                     hipStream_t s) {
-    int grid = (T + 3) / 4;
-    if (grid > 256 * 16) grid = 256 * 16;
-    const int row_bytes = H * (dt == MOE_BF16 ? 2 : 4);
     if (dt == MOE_BF16)
-        hipLaunchKernelGGL((combine_kernel<true>), dim3(grid), dim3(256), 0, s,
-                           static_cast<const uint8_t*>(y_perm), row_of_assign, gate,
-                           static_cast<const uint8_t*>(addend), static_cast<uint8_t*>(y), T, K,
-                           row_bytes, r_max);
+        launch_combine_t<true>(y_perm, row_of_assign, gate, addend, T, H, K, r_max, y, s);
     else
-        hipLaunchKernelGGL((combine_kernel<false>), dim3(grid), dim3(256), 0, s,
-                           static_cast<const uint8_t*>(y_perm), row_of_assign, gate,
-                           static_cast<const uint8_t*>(addend), static_cast<uint8_t*>(y), T, K,
-                           row_bytes, r_max);
+        launch_combine_t<false>(y_perm, row_of_assign, gate, addend, T, H, K, r_max, y, s);
 }
 
 }  // namespace moe

@@ -131,10 +131,14 @@ __global__ __launch_bounds__(256) void router_bf16_kernel(
     float* __restrict__ logits, int T, int H, int E, int K, int renorm,
     int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate) {
     constexpr int TOK = 16 * MB;      // tokens per workgroup
-    constexpr int LPR = 32 / MB;      // lanes covering one row slice
-    constexpr int KC = LPR * 8;       // hidden elements per slice
+    // MFMA k-steps per slice: 8 token loads in flight per lane where the weight
+    // fragments of a slice (KSTEPS * NB of them, kept in registers) allow it
+    constexpr int KSTEPS = (8 / MB < ((16 / NB) > 1 ? (16 / NB) : 1)) ? 8 / MB : ((16 / NB) > 1 ? (16 / NB) : 1);
+    constexpr int KC = 32 * KSTEPS;   // hidden elements per slice
+    constexpr int LPR = KC / 8;       // lanes covering one row slice
     constexpr int KCP = KC + 8;       // padded LDS row (elements)
-    constexpr int RPI = 2 * MB;       // rows per load instruction
+    constexpr int RPI = 64 / LPR;     // rows per load instruction
+    constexpr int NLD = TOK / RPI;    // token loads per lane per slice
     constexpr int EP = 16 * NB;       // experts padded to the MFMA N size
     __shared__ __attribute__((aligned(16))) bf16_t xs[4][TOK][KCP];
     __shared__ float red[TOK][EP + 1];
@@ -150,46 +154,55 @@ __global__ __launch_bounds__(256) void router_bf16_kernel(
         for (int b = 0; b < NB; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int lrow = lane / LPR, lcol = (lane % LPR) * 8;
-    u32x4 xr[8];
+    const int fr = lane & 15, fg = lane >> 4;  // fragment row / k-group
+    // both the token slice and the matching router-weight fragments of the NEXT
+    // slice are requested before the current slice is multiplied, so neither the
+    // HBM nor the L2 round trip sits in front of an MFMA
+    u32x4 xr[NLD], wr[KSTEPS][NB];
     auto load_chunk = [&](int c) {
         const int k = c * KC + lcol;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < NLD; ++i) {
             const int t = t0 + i * RPI + lrow;
             u32x4 v = u32x4{0u, 0u, 0u, 0u};
             if (t < T && k < H) v = *reinterpret_cast<const u32x4*>(x + (size_t)t * H + k);
             xr[i] = v;
         }
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            const int kw = c * KC + s * 32 + fg * 8;
+#pragma unroll
+            for (int b2 = 0; b2 < NB; ++b2) {
+                const int e = b2 * 16 + fr;
+                u32x4 v = u32x4{0u, 0u, 0u, 0u};
+                if (e < E && kw < H) v = *reinterpret_cast<const u32x4*>(w + (size_t)e * H + kw);
+                wr[s][b2] = v;
+            }
+        }
     };
 
     if (wave < nchunks) load_chunk(wave);
-    const int fr = lane & 15, fg = lane >> 4;  // fragment row / k-group
     for (int c = wave; c < nchunks; c += 4) {
+        bf16x8 bfrag[KSTEPS][NB];
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < NLD; ++i)
             *reinterpret_cast<u32x4*>(&xs[wave][i * RPI + lrow][lcol]) = xr[i];
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+            for (int b2 = 0; b2 < NB; ++b2) bfrag[s][b2] = __builtin_bit_cast(bf16x8, wr[s][b2]);
         if (c + 4 < nchunks) load_chunk(c + 4);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        const int kc0 = c * KC;
 #pragma unroll
-        for (int s = 0; s < KC / 32; ++s) {
-            bf16x8 bfrag[NB];
-            const int k = kc0 + s * 32 + fg * 8;
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const int e = b * 16 + fr;
-                u32x4 v = u32x4{0u, 0u, 0u, 0u};
-                if (e < E && k < H) v = *reinterpret_cast<const u32x4*>(w + (size_t)e * H + k);
-                bfrag[b] = __builtin_bit_cast(bf16x8, v);
-            }
+        for (int s = 0; s < KSTEPS; ++s) {
 #pragma unroll
             for (int a = 0; a < MB; ++a) {
                 const u32x4 av = *reinterpret_cast<const u32x4*>(&xs[wave][a * 16 + fr][s * 32 + fg * 8]);
                 const bf16x8 afrag = __builtin_bit_cast(bf16x8, av);
 #pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag[b], acc[a][b], 0, 0, 0);
+                for (int b2 = 0; b2 < NB; ++b2)
+                    acc[a][b2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag[s][b2], acc[a][b2], 0, 0, 0);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
