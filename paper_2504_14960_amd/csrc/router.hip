@@ -124,6 +124,77 @@ __device__ __forceinline__ void select_dispatch(const float* rows, int ld, int n
         select_block<4>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
 }
 
+// Selection with one LANE per token (K <= KSEL <= 8): the lane walks its
+// token's E logits once, keeping the KSEL best in a sorted register list
+// (insertion by compare-and-swap, so equal logits keep the lower index first),
+// then a second walk for the softmax denominator.  No cross-lane traffic at
+// all, which beats the butterfly version by a wide margin for E = 64: that one
+// spends its time waiting on chains of dependent cross-lane permutes.
+// `rows` must be LDS (row stride `ld`, odd => conflict-free); thread i of the
+// workgroup handles token i.
+template <int KSEL>
+__device__ __forceinline__ void select_lanes(const float* rows, int ld, int ntok, int t0, int T, int E,
+                                             int K, int renorm, int32_t* topk_idx, float* topk_gate) {
+    const int lt = threadIdx.x;
+    if (lt >= ntok || t0 + lt >= T) return;
+    const float* r = rows + (size_t)lt * ld;
+    float lv[KSEL];
+    int le[KSEL];
+#pragma unroll
+    for (int j = 0; j < KSEL; ++j) {
+        lv[j] = -INFINITY;
+        le[j] = 0x7fffffff;
+    }
+    for (int e = 0; e < E; ++e) {
+        float cv = r[e];
+        cv = (cv != cv) ? -INFINITY : cv;  // NaN ranks last
+        int ce = e;
+#pragma unroll
+        for (int j = 0; j < KSEL; ++j) {
+            const bool b = ranks_before(cv, ce, lv[j], le[j]);
+            const float tv = b ? lv[j] : cv;
+            const int te = b ? le[j] : ce;
+            lv[j] = b ? cv : lv[j];
+            le[j] = b ? ce : le[j];
+            cv = tv;
+            ce = te;
+        }
+    }
+    const float m = lv[0];
+    float z = 0.f;
+    for (int e = 0; e < E; ++e) {
+        float v = r[e];
+        v = (v != v) ? -INFINITY : v;
+        z += expf(v - m);
+    }
+    float p[KSEL], gsum = 0.f;
+#pragma unroll
+    for (int k = 0; k < KSEL; ++k) {
+        p[k] = expf(lv[k] - m) / z;
+        if (k < K) gsum += p[k];
+    }
+    const size_t o = (size_t)(t0 + lt) * K;
+#pragma unroll
+    for (int k = 0; k < KSEL; ++k)
+        if (k < K) {
+            topk_idx[o + k] = le[k];
+            topk_gate[o + k] = renorm ? p[k] / gsum : p[k];
+        }
+}
+
+// K <= 8: one lane per token; larger K: one lane group per token.
+__device__ __forceinline__ void select_tokens(const float* rows, int ld, int ntok, int t0, int T, int E,
+                                              int K, int renorm, int32_t* topk_idx, float* topk_gate) {
+    if (K <= 2)
+        select_lanes<2>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+    else if (K <= 4)
+        select_lanes<4>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+    else if (K <= 8)
+        select_lanes<8>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+    else
+        select_dispatch(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+}
+
 // ------------------------------------------------------------------ bf16 / MFMA
 template <int MB, int NB>
 __global__ __launch_bounds__(256) void router_bf16_kernel(
@@ -233,7 +304,7 @@ __global__ __launch_bounds__(256) void router_bf16_kernel(
         if (t0 + lt < T) logits[(size_t)(t0 + lt) * E + e] = v;
     }
     __syncthreads();
-    select_dispatch(&red[0][0], EP + 1, TOK, t0, T, E, K, renorm, topk_idx, topk_gate);
+    select_tokens(&red[0][0], EP + 1, TOK, t0, T, E, K, renorm, topk_idx, topk_gate);
 }
 
 // ------------------------------------------------------------------ fp32 / VALU
@@ -242,7 +313,7 @@ __global__ __launch_bounds__(256) void router_f32_kernel(
     const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ bias,
     float* __restrict__ logits, int T, int H, int E, int K, int renorm,
     int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate) {
-    __shared__ float red[4][kMaxExperts];
+    __shared__ float red[4][kMaxExperts + 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int t0 = blockIdx.x * 4;
     const int t = t0 + wave;
@@ -268,7 +339,7 @@ __global__ __launch_bounds__(256) void router_f32_kernel(
         }
     }
     __syncthreads();
-    select_dispatch(&red[0][0], kMaxExperts, 4, t0, T, E, K, renorm, topk_idx, topk_gate);
+    select_tokens(&red[0][0], kMaxExperts + 1, 4, t0, T, E, K, renorm, topk_idx, topk_gate);
 }
 
 // ------------------------------------------------------------------ selection only
@@ -276,10 +347,24 @@ __global__ __launch_bounds__(256) void topk_only_kernel(const float* __restrict_
                                                         int E, int K, int renorm,
                                                         int32_t* __restrict__ topk_idx,
                                                         float* __restrict__ topk_gate) {
-    const int G = group_lanes(E);
-    const int per_block = 4 * (64 / G);
-    for (int t0 = blockIdx.x * per_block; t0 < T; t0 += gridDim.x * per_block)
-        select_dispatch(logits + (size_t)t0 * E, E, per_block, t0, T, E, K, renorm, topk_idx, topk_gate);
+    // a tile of tokens is copied to LDS with coalesced loads (row stride odd),
+    // then selected from there
+    constexpr int kTileFloats = 12288;
+    __shared__ float tile[kTileFloats];
+    const int ld = E | 1;
+    int per_block = kTileFloats / ld;
+    if (per_block > 256) per_block = 256;
+    for (int t0 = blockIdx.x * per_block; t0 < T; t0 += gridDim.x * per_block) {
+        const int ntok = min(per_block, T - t0);
+        const float* src = logits + (size_t)t0 * E;
+        for (int i = threadIdx.x; i < ntok * E; i += 256) {
+            const int lt = i / E, e = i - lt * E;
+            tile[lt * ld + e] = src[i];
+        }
+        __syncthreads();
+        select_tokens(tile, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+        __syncthreads();
+    }
 }
 
 template <int MB, int NB>
@@ -297,7 +382,8 @@ void launch_router(const void* x, const void* w, const float* bias, float* logit
                    int E, int K, int renorm, moe_dtype_t dt, int32_t* idx, float* gate,
                    hipStream_t s) {
     if (x == nullptr) {
-        const int per_block = 4 * (64 / group_lanes(E));
+        int per_block = 12288 / (E | 1);
+        if (per_block > 256) per_block = 256;
         int grid = (T + per_block - 1) / per_block;
         if (grid > 4096) grid = 4096;
         hipLaunchKernelGGL(topk_only_kernel, dim3(grid), dim3(256), 0, s, logits, T, E, K, renorm, idx, gate);
