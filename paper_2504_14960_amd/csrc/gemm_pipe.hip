@@ -213,6 +213,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe_kernel(
         uint8_t* nxt = smem + ((kt & 1) ^ 1) * STAGE;
         const int kbyte = (kt + 1) * BK * 2;
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (LMODE == 3) {
+            // late barrier: the loads get all four k-steps to land; the price is
+            // that the next tile's first fragments are read with nothing to hide them
+            kstep(0, true, cur, 1, 2, 0, LB, 1, kbyte, nxt);
+            kstep(1, true, cur, 2, 2, LB, NLOAD, 1, kbyte, nxt);
+            kstep(0, true, cur, 3, 2, 0, 0, 0, kbyte, nxt);
+            kstep(1, false, cur, 0, 0, 0, 0, 0, kbyte, nxt);
+            __builtin_amdgcn_s_waitcnt(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < NREAD; ++q) read_one(nxt, 0, 0, (FM == FN) ? ((q & 1) ? FM + q / 2 : q / 2) : q);  // A0,B0,A1,B1,... when square
+            continue;
+        }
         kstep(0, true, cur, 1, 2, LA, LB, LPS, kbyte, nxt);      // k-step 0
         kstep(1, true, cur, 2, 2, LB, NLOAD, LPS, kbyte, nxt);   // k-step 1
         kstep(0, true, cur, 3, 2, 0, 0, 0, kbyte, nxt);          // k-step 2
@@ -299,6 +313,8 @@ bool launch_pipe_ffn(const void* x_perm, const int32_t* offsets, int r_max, int 
         case 15: run_pipe_pair<128, 128, 2, 2, 0>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         case 16: run_pipe_pair<256, 256, 2, 2, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         case 17: run_pipe_pair<256, 256, 2, 4, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 22: run_pipe_pair<256, 256, 2, 2, 3>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 23: run_pipe_pair<256, 256, 2, 4, 3>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         case 20: run_pipe_pair<256, 256, 2, 2, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         case 21: run_pipe_pair<256, 256, 2, 4, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         default: return false;
