@@ -82,6 +82,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe_kernel(
 
     auto fetch_one = [&](int i, int kbyte, uint8_t* st) {
         // i-th direct load of a k-tile: A passes first, then B passes
+#ifdef MOE_PIPE_SKIPB
+        if (i >= PA && kbyte != 0) return;  // diagnostic build: half the load traffic, wrong results
+#endif
         if (i < PA) {
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void*)(a_base + kbyte + a_goff[i]),
