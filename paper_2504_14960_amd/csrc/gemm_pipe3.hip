@@ -1,0 +1,274 @@
+// Grouped expert GEMM (a3), pipelined kernel with uneven LDS staging: three
+// stages for the activation tile, two for the weight tile (3 x 32 KiB + 2 x
+// 32 KiB = all 160 KiB of a CU's LDS for a 256 x 256 x 64 tile).
+//
+// Why: the direct global->LDS path of one CU moves ~40-50 B/clk, and a 256x256
+// tile needs 64 KiB per 64-wide k-tile, so that path is busy for most of a
+// k-tile.  With two stages for both operands every load of tile t+1 has to
+// have landed by the single barrier of tile t, and the waves queue up behind
+// the texture unit there.  Here only the weight tile of t+1 (issued first in
+// each period) has to be complete at the barrier; the activation tile fetched
+// in the same period is the one for t+2 and gets a whole extra period to land
+// (`s_waitcnt vmcnt(PA)` leaves exactly those loads in flight).
+//
+// Everything else (XOR-swizzled 128-byte LDS rows, 32x32x16 bf16 MFMA with
+// the weight fragment first, fragment double buffering, source-ordered
+// interleave frozen by scheduling barriers, ragged tile scheduler, fused
+// SwiGLU epilogue) is as in gemm_pipe.hip.
+#include "gemm_tile.h"
+
+namespace moe {
+
+namespace {
+
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, int DIST>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
+    const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
+    const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, int ntn) {
+    constexpr int BK = 64;
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int CPR = BK / 8;
+    constexpr int RPP = NT / CPR;
+    constexpr int PA = BM / RPP, PB = BN / RPP;
+    constexpr int ROWB = BK * 2;
+    constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
+    constexpr int B_REGION = 3 * A_BYTES;      // B slots start after the three A slots
+    constexpr int OUTN = SWIGLU ? BN / 2 : BN;
+    constexpr int NLOAD = PA + PB;             // direct loads per thread per period
+    constexpr int NREAD = FM + FN;
+    constexpr int NMFMA = FM * FN;
+    constexpr int NSLOT = NREAD;
+    constexpr int MPS = NMFMA / NSLOT;
+    // how a period's NLOAD loads (weight tile first) are spread over the k-steps
+    // 3 (of the previous tile), 0, 1, 2:
+    //   DIST 0: thirds under k-steps 3, 0, 1, one per slot
+    //   DIST 1: quarters under all four k-steps, evenly spaced slots
+    constexpr int LA = (DIST == 1) ? NLOAD / 4 : NLOAD / 3;                     // under k-step 3 (previous tile)
+    constexpr int LB = (DIST == 1) ? NLOAD / 2 : LA + (NLOAD - LA + 1) / 2;     // end of k-step 0's share
+    constexpr int LC = (DIST == 1) ? 3 * NLOAD / 4 : NLOAD;                     // end of k-step 1's share
+    constexpr int LSTRIDE = (DIST == 1) ? NSLOT / ((NLOAD + 3) / 4) : 1;        // slots between two loads
+    static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must divide into fetch passes");
+    static_assert(!SWIGLU || ((BN / 2) % RPP == 0 && FN % 2 == 0), "gate/up halves must be pass- and fragment-aligned");
+    static_assert(LA <= PB, "only weight-tile loads may be issued before the barrier's successor step");
+    static_assert(LSTRIDE >= 1 && (LB - LA) * LSTRIDE <= NSLOT && (LC - LB) * LSTRIDE <= NSLOT &&
+                      (NLOAD - LC) * LSTRIDE <= NSLOT && LA * LSTRIDE <= NSLOT, "not enough slots for the loads");
+    static_assert(PA < 64, "vmcnt holds 6 bits");
+
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    // the tile scheduler's scratch lives in the second weight slot, which is not
+    // written before the prologue's barrier
+    int* sched = reinterpret_cast<int*>(smem + B_REGION + B_BYTES);
+
+    const Tile tile = find_tile<BM>(offsets, E, ntn, sched);
+    if (!tile.valid) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int n0 = tile.ntile * OUTN;
+
+    const int frow = tid / CPR, fchunk = tid % CPR;
+    const uint8_t* a_base = reinterpret_cast<const uint8_t*>(A + (size_t)tile.row0 * K);
+    const size_t b_row0 = ((size_t)tile.expert * N + n0) * K;
+    const uint8_t* b_base0 = reinterpret_cast<const uint8_t*>(B0 + b_row0);
+    const uint8_t* b_base1 = SWIGLU ? reinterpret_cast<const uint8_t*>(B1 + b_row0) : b_base0;
+    uint32_t a_goff[PA], b_goff[PB];
+#pragma unroll
+    for (int p = 0; p < PA; ++p) {
+        const int r = p * RPP + frow;
+        const int rr = min(r, tile.rows - 1);  // ragged tail: re-read a valid row, result discarded
+        a_goff[p] = (uint32_t)rr * (uint32_t)K * 2u + (uint32_t)((fchunk ^ (r & 7)) * 16);
+    }
+#pragma unroll
+    for (int p = 0; p < PB; ++p) {
+        const int r = p * RPP + frow;
+        int f = SWIGLU ? (r % (BN / 2)) : r;
+        f = min(f, N - 1 - n0);
+        b_goff[p] = (uint32_t)f * (uint32_t)K * 2u + (uint32_t)((fchunk ^ (r & 7)) * 16);
+    }
+    const int wbase = (wave * 64 / CPR) * ROWB;
+
+    // load i of a period: i < PB -> pass i of the weight tile (k offset kb_b, slot
+    // ld_b), else pass i-PB of the activation tile (k offset kb_a, slot ld_a)
+    auto fetch_one = [&](int i, int kb_b, int kb_a, uint8_t* ld_b, uint8_t* ld_a) {
+        if (i < PB) {
+            const uint8_t* base = (SWIGLU && i >= PB / 2) ? b_base1 : b_base0;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(base + kb_b + b_goff[i]),
+                (__attribute__((address_space(3))) void*)(ld_b + i * RPP * ROWB + wbase), 16, 0, 0);
+        } else {
+            const int p = i - PB;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(a_base + kb_a + a_goff[p]),
+                (__attribute__((address_space(3))) void*)(ld_a + p * RPP * ROWB + wbase), 16, 0, 0);
+        }
+    };
+
+    const int fr = lane & 31, fk = lane >> 5;
+    int a_off[FM], b_off[FN], a_sw[FM], b_sw[FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int r = wm * WM + i * 32 + fr;
+        a_off[i] = r * ROWB;
+        a_sw[i] = r & 7;
+    }
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        int r;
+        if (SWIGLU) {
+            constexpr int half = FN / 2;
+            r = (j < half) ? (wn * (WN / 2) + j * 32 + fr) : (BN / 2 + wn * (WN / 2) + (j - half) * 32 + fr);
+        } else {
+            r = wn * WN + j * 32 + fr;
+        }
+        b_off[j] = r * ROWB;
+        b_sw[j] = r & 7;
+    }
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    bf16x8 af[2][FM], bfg[2][FN];
+    auto read_one = [&](const uint8_t* sa, const uint8_t* sb, int s, int buf, int q) {
+        const int c = 2 * s + fk;
+        if (q < FM)
+            af[buf][q] = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const u32x4*>(sa + a_off[q] + ((c ^ a_sw[q]) << 4)));
+        else
+            bfg[buf][q - FM] = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const u32x4*>(sb + b_off[q - FM] + ((c ^ b_sw[q - FM]) << 4)));
+    };
+    auto mfma_one = [&](int buf, int m) {
+        const int i = m / FN, j = m % FN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfg[buf][j], af[buf][i], acc[i][j], 0, 0, 0);
+    };
+    // one k-step in issue order: NSLOT slots of {MPS MFMAs on set mf_buf; up to
+    // 2 fragment reads of k-step rd_s into the other set; one direct load}
+    auto kstep = [&](int mf_buf, const uint8_t* rd_a, const uint8_t* rd_b, int rd_s, int ld_begin, int ld_end,
+                     int kb_b, int kb_a, uint8_t* ld_b, uint8_t* ld_a) {
+        int m = 0, rd = 0, ld = ld_begin;
+#pragma unroll
+        for (int slot = 0; slot < NSLOT; ++slot) {
+#pragma unroll
+            for (int q = 0; q < MPS; ++q) {
+                mfma_one(mf_buf, m);
+                ++m;
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                if (rd < NREAD) {
+                    read_one(rd_a, rd_b, rd_s, mf_buf ^ 1, rd);
+                    ++rd;
+                }
+            if (slot % LSTRIDE == 0 && ld < ld_end) {
+                fetch_one(ld, kb_b, kb_a, ld_b, ld_a);
+                ++ld;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int mm = NSLOT * MPS; mm < NMFMA; ++mm) mfma_one(mf_buf, mm);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    const int KT = K / BK;
+    auto kb = [&](int kt) { return min(kt, KT - 1) * (BK * 2); };  // past the end: the last tile again, never used
+    uint8_t* const b_region = smem + B_REGION;
+
+    // prologue: A(0), B(0), then A(1); only the first two must have landed
+#pragma unroll
+    for (int i = PB; i < NLOAD; ++i) fetch_one(i, 0, kb(0), b_region, smem);
+#pragma unroll
+    for (int i = 0; i < PB; ++i) fetch_one(i, kb(0), 0, b_region, smem);
+#pragma unroll
+    for (int i = PB; i < NLOAD; ++i) fetch_one(i, 0, kb(1), b_region, smem + A_BYTES);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (PA & 0xF) | ((PA >> 4) << 14));  // vmcnt(PA)
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < NREAD; ++q) read_one(smem, b_region, 0, 0, q);
+    // first loads of period 0: the head of B(1) into weight slot 1
+#pragma unroll
+    for (int i = 0; i < LA; ++i) fetch_one(i, kb(1), 0, b_region + B_BYTES, smem);
+
+    int a0 = 0, a1 = A_BYTES, a2 = 2 * A_BYTES;  // byte offsets of the A slots of tiles kt, kt+1, kt+2
+    int b0 = 0, b1 = B_BYTES;                    // B slots of tiles kt, kt+1
+    for (int kt = 0; kt < KT; ++kt) {
+        const uint8_t* ca = smem + a0;
+        const uint8_t* cb = b_region + b0;
+        uint8_t* lb = b_region + b1;  // B(kt+1)
+        uint8_t* la = smem + a2;      // A(kt+2)
+        const int kbb = kb(kt + 1), kba = kb(kt + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        kstep(0, ca, cb, 1, LA, LB, kbb, kba, lb, la);     // k-step 0
+        kstep(1, ca, cb, 2, LB, LC, kbb, kba, lb, la);     // k-step 1
+        kstep(0, ca, cb, 3, LC, NLOAD, kbb, kba, lb, la);  // k-step 2
+        // B(kt+1) was issued before A(kt+2) in this period and A(kt+1) a period
+        // ago: all but the PA youngest loads must have landed; this wave's reads
+        // of tile kt are in registers (lgkmcnt(0))
+        __builtin_amdgcn_s_waitcnt((PA & 0xF) | ((PA >> 4) << 14));
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 3: first fragments of tile kt+1; tile kt's weight slot is free,
+        // the head of B(kt+2) goes into it
+        kstep(1, smem + a1, b_region + b1, 0, 0, LA, kb(kt + 2), 0, b_region + b0, smem);
+        const int ta = a0;
+        a0 = a1;
+        a1 = a2;
+        a2 = ta;
+        const int tb = b0;
+        b0 = b1;
+        b1 = tb;
+    }
+    wait_vmcnt0();  // loads past the end of K may still be landing in LDS
+    store_tile<FM, FN, WM, WN, BN, SWIGLU>(acc, tile, C, N, n0, wm, wn, lane);
+}
+
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, int DIST>
+void launch_pipe3(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B0,
+                  const void* B1, void* C, hipStream_t s) {
+    constexpr int OUTN = SWIGLU ? BN / 2 : BN;
+    constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
+    const int ntn = (N + OUTN - 1) / OUTN;
+    auto kern = gemm_bf16_pipe3_kernel<BM, BN, WGM, WGN, SWIGLU, DIST>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        attr_set = true;
+    }
+    const int grid = grid_for(r_max, E, BM, ntn);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A),
+                       offsets, E, N, K, static_cast<const bf16_t*>(B0),
+                       static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C), ntn);
+}
+
+template <int BM, int BN, int WGM, int WGN, int DIST>
+void run_pipe3_pair(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                    const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm,
+                    int phase, hipStream_t s) {
+    if (phase & 1) launch_pipe3<BM, BN, WGM, WGN, true, DIST>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, s);
+    if (phase & 2) launch_pipe3<BM, BN, WGM, WGN, false, DIST>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
+}
+
+}  // namespace
+
+bool launch_pipe3_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                      const void* w_gate, const void* w_up, const void* w_down, void* h,
+                      void* y_perm, int variant, int phase, hipStream_t s) {
+    switch (variant) {
+        case 30: run_pipe3_pair<256, 256, 2, 2, 0>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 31: run_pipe3_pair<256, 256, 2, 4, 0>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 32: run_pipe3_pair<256, 256, 2, 2, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 33: run_pipe3_pair<256, 256, 2, 4, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        default: return false;
+    }
+}
+
+}  // namespace moe

@@ -69,12 +69,27 @@ __device__ __forceinline__ Tile find_tile(const int32_t* __restrict__ offsets, i
     __syncthreads();
     const int e = sh[kMaxExperts + 1];
     const int mt_e = sh[e + 1] - sh[e];
-    const long long Le = L - (long long)sh[e] * ntn;
-    const int mg = (int)(Le / ((long long)MG * ntn));
-    const int rem = (int)(Le - (long long)mg * MG * ntn);
-    const int gsz = min(MG, mt_e - mg * MG);
+    const int Le = (int)(L - (long long)sh[e] * ntn);
+    // the expert's M-tiles are cut into ceil(mt/MG) groups of (nearly) equal size,
+    // so that no group is left with a single M-tile (a 1 x 32 block of tiles
+    // shares almost nothing in L2)
+    const int ng = (mt_e + MG - 1) / MG;
+    const int gbase = mt_e / ng, grem = mt_e % ng;   // the first grem groups hold gbase + 1 tiles
+    const int big = grem * (gbase + 1) * ntn;        // tiles in those larger groups
+    int g, gsz, m_first, rem;
+    if (Le < big) {
+        gsz = gbase + 1;
+        g = Le / (gsz * ntn);
+        rem = Le - g * gsz * ntn;
+        m_first = g * gsz;
+    } else {
+        gsz = gbase;
+        g = (Le - big) / (gsz * ntn);
+        rem = (Le - big) - g * gsz * ntn;
+        m_first = grem * (gbase + 1) + g * gsz;
+    }
     const int n = rem / gsz;
-    const int m = mg * MG + rem - n * gsz;
+    const int m = m_first + rem - n * gsz;
     const int lo = offsets[e], hi = offsets[e + 1];
     t.expert = e;
     t.row0 = lo + m * BM;
@@ -153,5 +168,10 @@ inline int grid_for(int r_max, int E, int BM, int ntn) {
 bool launch_pipe_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                      const void* w_gate, const void* w_up, const void* w_down, void* h,
                      void* y_perm, int variant, int phase, hipStream_t s);
+
+// pipelined MFMA kernels with three activation stages (gemm_pipe3.hip)
+bool launch_pipe3_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                      const void* w_gate, const void* w_up, const void* w_down, void* h,
+                      void* y_perm, int variant, int phase, hipStream_t s);
 
 }  // namespace moe

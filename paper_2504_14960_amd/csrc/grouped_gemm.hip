@@ -353,13 +353,15 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
         return true;
     }
     if (variant == 0) {
-        // tuned defaults (Mixtral-8x22B layer shape on MI355X): the 8-wave pipelined
-        // kernel for the gate/up GEMM, the 4-wave one for the down projection
+        // tuned defaults (Mixtral-8x22B layer shape on MI355X): the kernels with three
+        // activation stages, 8 waves for the gate/up GEMM, 4 waves for the down projection
         bool ok = true;
-        if (phase & 1) ok = ok && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 21, 1, s);
-        if (phase & 2) ok = ok && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 20, 2, s);
+        if (phase & 1) ok = ok && launch_pipe3_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 31, 1, s);
+        if (phase & 2) ok = ok && launch_pipe3_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 30, 2, s);
         return ok;
     }
+    if (variant >= 30 && launch_pipe3_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, variant, phase, s))
+        return true;
     if (variant >= 10 && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, variant, phase, s))
         return true;
     switch (variant) {
