@@ -19,9 +19,14 @@
 
 namespace moe {
 
+#ifdef MOE_PIPE_TIMING
+// instrumentation build only: per-wave tick counters {loop, load wait, barrier wait}
+__device__ unsigned long long g_pipe3_ticks[4096 * 8 * 4];
+#endif
+
 namespace {
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU, int DIST>
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, int DIST, bool TRI_B = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, int ntn) {
@@ -34,7 +39,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     constexpr int PA = BM / RPP, PB = BN / RPP;
     constexpr int ROWB = BK * 2;
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
-    constexpr int B_REGION = 3 * A_BYTES;      // B slots start after the three A slots
+    // TRI_B = false: three activation slots + two weight slots (the weight tile
+    // is the "early" operand that must be complete at the barrier);
+    // TRI_B = true: the roles are swapped
+    constexpr int A_SLOTS = TRI_B ? 2 : 3, B_SLOTS = TRI_B ? 3 : 2;
+    constexpr int B_REGION = A_SLOTS * A_BYTES;  // B slots start after the A slots
+    constexpr int PE = TRI_B ? PA : PB;          // passes of the early (2-slot) operand
+    constexpr int PL = TRI_B ? PB : PA;          // passes of the late (3-slot) operand
+    constexpr int E_BYTES = TRI_B ? A_BYTES : B_BYTES, L_BYTES = TRI_B ? B_BYTES : A_BYTES;
     constexpr int OUTN = SWIGLU ? BN / 2 : BN;
     constexpr int NLOAD = PA + PB;             // direct loads per thread per period
     constexpr int NREAD = FM + FN;
@@ -51,15 +63,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     constexpr int LSTRIDE = (DIST == 1) ? NSLOT / ((NLOAD + 3) / 4) : 1;        // slots between two loads
     static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must divide into fetch passes");
     static_assert(!SWIGLU || ((BN / 2) % RPP == 0 && FN % 2 == 0), "gate/up halves must be pass- and fragment-aligned");
-    static_assert(LA <= PB, "only weight-tile loads may be issued before the barrier's successor step");
+    static_assert(LA <= PE, "only early-operand loads may be issued under k-step 3");
     static_assert(LSTRIDE >= 1 && (LB - LA) * LSTRIDE <= NSLOT && (LC - LB) * LSTRIDE <= NSLOT &&
                       (NLOAD - LC) * LSTRIDE <= NSLOT && LA * LSTRIDE <= NSLOT, "not enough slots for the loads");
-    static_assert(PA < 64, "vmcnt holds 6 bits");
+    static_assert(PL < 64, "vmcnt holds 6 bits");
+    static_assert(A_SLOTS * A_BYTES + B_SLOTS * B_BYTES <= 160 * 1024, "tile stages exceed the 160 KiB of LDS");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     // the tile scheduler's scratch lives in the second weight slot, which is not
     // written before the prologue's barrier
-    int* sched = reinterpret_cast<int*>(smem + B_REGION + B_BYTES);
+    int* sched = reinterpret_cast<int*>(smem + (TRI_B ? A_BYTES : B_REGION + B_BYTES));  // second early slot
 
     const Tile tile = find_tile<BM>(offsets, E, ntn, sched);
     if (!tile.valid) return;
@@ -90,19 +103,24 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     }
     const int wbase = (wave * 64 / CPR) * ROWB;
 
-    // load i of a period: i < PB -> pass i of the weight tile (k offset kb_b, slot
-    // ld_b), else pass i-PB of the activation tile (k offset kb_a, slot ld_a)
-    auto fetch_one = [&](int i, int kb_b, int kb_a, uint8_t* ld_b, uint8_t* ld_a) {
-        if (i < PB) {
-            const uint8_t* base = (SWIGLU && i >= PB / 2) ? b_base1 : b_base0;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(base + kb_b + b_goff[i]),
-                (__attribute__((address_space(3))) void*)(ld_b + i * RPP * ROWB + wbase), 16, 0, 0);
+    auto fetch_a = [&](int p, int kbyte, uint8_t* st) {
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(a_base + kbyte + a_goff[p]),
+            (__attribute__((address_space(3))) void*)(st + p * RPP * ROWB + wbase), 16, 0, 0);
+    };
+    auto fetch_b = [&](int p, int kbyte, uint8_t* st) {
+        const uint8_t* base = (SWIGLU && p >= PB / 2) ? b_base1 : b_base0;
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(base + kbyte + b_goff[p]),
+            (__attribute__((address_space(3))) void*)(st + p * RPP * ROWB + wbase), 16, 0, 0);
+    };
+    // load i of a period: i < PE -> pass i of the early operand (k offset kb_e,
+    // slot ld_e), else pass i-PE of the late operand (k offset kb_l, slot ld_l)
+    auto fetch_one = [&](int i, int kb_e, int kb_l, uint8_t* ld_e, uint8_t* ld_l) {
+        if (i < PE) {
+            if (TRI_B) fetch_a(i, kb_e, ld_e); else fetch_b(i, kb_e, ld_e);
         } else {
-            const int p = i - PB;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(a_base + kb_a + a_goff[p]),
-                (__attribute__((address_space(3))) void*)(ld_a + p * RPP * ROWB + wbase), 16, 0, 0);
+            if (TRI_B) fetch_b(i - PE, kb_l, ld_l); else fetch_a(i - PE, kb_l, ld_l);
         }
     };
 
@@ -180,63 +198,89 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
 
     const int KT = K / BK;
     auto kb = [&](int kt) { return min(kt, KT - 1) * (BK * 2); };  // past the end: the last tile again, never used
-    uint8_t* const b_region = smem + B_REGION;
+    uint8_t* const e_region = smem + (TRI_B ? 0 : B_REGION);   // early operand: 2 slots
+    uint8_t* const l_region = smem + (TRI_B ? B_REGION : 0);   // late operand: 3 slots
+    auto a_ptr = [&](int e_off, int l_off) -> const uint8_t* { return TRI_B ? e_region + e_off : l_region + l_off; };
+    auto b_ptr = [&](int e_off, int l_off) -> const uint8_t* { return TRI_B ? l_region + l_off : e_region + e_off; };
 
-    // prologue: A(0), B(0), then A(1); only the first two must have landed
+    // prologue: late(0), early(0), then late(1); only the first two must have landed
 #pragma unroll
-    for (int i = PB; i < NLOAD; ++i) fetch_one(i, 0, kb(0), b_region, smem);
+    for (int i = PE; i < NLOAD; ++i) fetch_one(i, 0, kb(0), e_region, l_region);
 #pragma unroll
-    for (int i = 0; i < PB; ++i) fetch_one(i, kb(0), 0, b_region, smem);
+    for (int i = 0; i < PE; ++i) fetch_one(i, kb(0), 0, e_region, l_region);
 #pragma unroll
-    for (int i = PB; i < NLOAD; ++i) fetch_one(i, 0, kb(1), b_region, smem + A_BYTES);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (PA & 0xF) | ((PA >> 4) << 14));  // vmcnt(PA)
+    for (int i = PE; i < NLOAD; ++i) fetch_one(i, 0, kb(1), e_region, l_region + L_BYTES);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (PL & 0xF) | ((PL >> 4) << 14));  // vmcnt(PL)
     __syncthreads();
 #pragma unroll
-    for (int q = 0; q < NREAD; ++q) read_one(smem, b_region, 0, 0, q);
-    // first loads of period 0: the head of B(1) into weight slot 1
+    for (int q = 0; q < NREAD; ++q) read_one(a_ptr(0, 0), b_ptr(0, 0), 0, 0, q);
+    // first loads of period 0: the head of early(1) into early slot 1
 #pragma unroll
-    for (int i = 0; i < LA; ++i) fetch_one(i, kb(1), 0, b_region + B_BYTES, smem);
+    for (int i = 0; i < LA; ++i) fetch_one(i, kb(1), 0, e_region + E_BYTES, l_region);
 
-    int a0 = 0, a1 = A_BYTES, a2 = 2 * A_BYTES;  // byte offsets of the A slots of tiles kt, kt+1, kt+2
-    int b0 = 0, b1 = B_BYTES;                    // B slots of tiles kt, kt+1
+    int l0 = 0, l1 = L_BYTES, l2 = 2 * L_BYTES;  // late-operand slots of tiles kt, kt+1, kt+2
+    int e0 = 0, e1 = E_BYTES;                    // early-operand slots of tiles kt, kt+1
+#ifdef MOE_PIPE_TIMING
+    unsigned long long tk_wait = 0, tk_bar = 0;
+    const unsigned long long tk_begin = __builtin_amdgcn_s_memtime();
+#endif
     for (int kt = 0; kt < KT; ++kt) {
-        const uint8_t* ca = smem + a0;
-        const uint8_t* cb = b_region + b0;
-        uint8_t* lb = b_region + b1;  // B(kt+1)
-        uint8_t* la = smem + a2;      // A(kt+2)
-        const int kbb = kb(kt + 1), kba = kb(kt + 2);
+        const uint8_t* ca = a_ptr(e0, l0);
+        const uint8_t* cb = b_ptr(e0, l0);
+        uint8_t* le = e_region + e1;  // early(kt+1)
+        uint8_t* ll = l_region + l2;  // late(kt+2)
+        const int kbe = kb(kt + 1), kbl = kb(kt + 2);
         __builtin_amdgcn_sched_barrier(0);
-        kstep(0, ca, cb, 1, LA, LB, kbb, kba, lb, la);     // k-step 0
-        kstep(1, ca, cb, 2, LB, LC, kbb, kba, lb, la);     // k-step 1
-        kstep(0, ca, cb, 3, LC, NLOAD, kbb, kba, lb, la);  // k-step 2
-        // B(kt+1) was issued before A(kt+2) in this period and A(kt+1) a period
-        // ago: all but the PA youngest loads must have landed; this wave's reads
-        // of tile kt are in registers (lgkmcnt(0))
-        __builtin_amdgcn_s_waitcnt((PA & 0xF) | ((PA >> 4) << 14));
+        kstep(0, ca, cb, 1, LA, LB, kbe, kbl, le, ll);     // k-step 0
+        kstep(1, ca, cb, 2, LB, LC, kbe, kbl, le, ll);     // k-step 1
+        kstep(0, ca, cb, 3, LC, NLOAD, kbe, kbl, le, ll);  // k-step 2
+        // early(kt+1) was issued before late(kt+2) in this period and late(kt+1) a
+        // period ago: all but the PL youngest loads must have landed; this wave's
+        // reads of tile kt are in registers (lgkmcnt(0))
+#ifdef MOE_PIPE_TIMING
+        const unsigned long long tk0 = __builtin_amdgcn_s_memtime();
+        __builtin_amdgcn_s_waitcnt((PL & 0xF) | ((PL >> 4) << 14));
+        const unsigned long long tk1 = __builtin_amdgcn_s_memtime();
         __builtin_amdgcn_s_barrier();
+        const unsigned long long tk2 = __builtin_amdgcn_s_memtime();
+        tk_wait += tk1 - tk0;
+        tk_bar += tk2 - tk1;
+#else
+        __builtin_amdgcn_s_waitcnt((PL & 0xF) | ((PL >> 4) << 14));
+        __builtin_amdgcn_s_barrier();
+#endif
         __builtin_amdgcn_sched_barrier(0);
-        // k-step 3: first fragments of tile kt+1; tile kt's weight slot is free,
-        // the head of B(kt+2) goes into it
-        kstep(1, smem + a1, b_region + b1, 0, 0, LA, kb(kt + 2), 0, b_region + b0, smem);
-        const int ta = a0;
-        a0 = a1;
-        a1 = a2;
-        a2 = ta;
-        const int tb = b0;
-        b0 = b1;
-        b1 = tb;
+        // k-step 3: first fragments of tile kt+1; tile kt's early slot is free,
+        // the head of early(kt+2) goes into it
+        kstep(1, a_ptr(e1, l1), b_ptr(e1, l1), 0, 0, LA, kb(kt + 2), 0, e_region + e0, l_region);
+        const int tl = l0;
+        l0 = l1;
+        l1 = l2;
+        l2 = tl;
+        const int te = e0;
+        e0 = e1;
+        e1 = te;
     }
+#ifdef MOE_PIPE_TIMING
+    if (lane == 0 && blockIdx.x < 4096) {
+        unsigned long long* o = g_pipe3_ticks + ((size_t)blockIdx.x * 8 + wave) * 4;
+        o[0] = __builtin_amdgcn_s_memtime() - tk_begin;
+        o[1] = tk_wait;
+        o[2] = tk_bar;
+        o[3] = tk_begin;
+    }
+#endif
     wait_vmcnt0();  // loads past the end of K may still be landing in LDS
     store_tile<FM, FN, WM, WN, BN, SWIGLU>(acc, tile, C, N, n0, wm, wn, lane);
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU, int DIST>
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, int DIST, bool TRI_B>
 void launch_pipe3(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B0,
                   const void* B1, void* C, hipStream_t s) {
     constexpr int OUTN = SWIGLU ? BN / 2 : BN;
-    constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
+    constexpr size_t smem = (size_t)(TRI_B ? 2 * BM + 3 * BN : 3 * BM + 2 * BN) * 64 * 2;
     const int ntn = (N + OUTN - 1) / OUTN;
-    auto kern = gemm_bf16_pipe3_kernel<BM, BN, WGM, WGN, SWIGLU, DIST>;
+    auto kern = gemm_bf16_pipe3_kernel<BM, BN, WGM, WGN, SWIGLU, DIST, TRI_B>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -249,12 +293,12 @@ void launch_pipe3(const void* A, const int32_t* offsets, int r_max, int E, int N
                        static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C), ntn);
 }
 
-template <int BM, int BN, int WGM, int WGN, int DIST>
+template <int BM, int BN, int WGM, int WGN, int DIST, bool TRI_B = false>
 void run_pipe3_pair(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                     const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm,
                     int phase, hipStream_t s) {
-    if (phase & 1) launch_pipe3<BM, BN, WGM, WGN, true, DIST>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, s);
-    if (phase & 2) launch_pipe3<BM, BN, WGM, WGN, false, DIST>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
+    if (phase & 1) launch_pipe3<BM, BN, WGM, WGN, true, DIST, TRI_B>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, s);
+    if (phase & 2) launch_pipe3<BM, BN, WGM, WGN, false, DIST, TRI_B>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
 }
 
 }  // namespace
@@ -267,6 +311,8 @@ bool launch_pipe3_ffn(const void* x_perm, const int32_t* offsets, int r_max, int
         case 31: run_pipe3_pair<256, 256, 2, 4, 0>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         case 32: run_pipe3_pair<256, 256, 2, 2, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         case 33: run_pipe3_pair<256, 256, 2, 4, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 34: run_pipe3_pair<256, 256, 2, 2, 0, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 35: run_pipe3_pair<256, 256, 2, 4, 0, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         default: return false;
     }
 }

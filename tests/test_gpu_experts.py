@@ -8,7 +8,7 @@ from helpers import assert_close, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
-ALL_VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 12, 13, 14, 15, 16, 17, 20, 21, 22, 23, 30, 31, 32, 33, 99]
+ALL_VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 12, 13, 14, 15, 16, 17, 20, 21, 22, 23, 30, 31, 32, 33, 34, 35, 99]
 
 
 def _offsets(counts):
