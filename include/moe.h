@@ -202,7 +202,9 @@ moe_status_t moe_layer_forward(const void* x, const void* w_router, const float*
 
 /* Tuning knobs for experiments (process-wide, not thread-safe; defaults are
  * the tuned ones).  Unknown names return MOE_ERR_INVALID_ARG.  Names:
- * "gemm_variant" (0 = auto). */
+ * "gemm_variant" (0 = auto); "gemm_workgroups" (workgroups launched by the
+ * persistent grouped-GEMM kernels; 0 = one per compute unit, values below 8
+ * are raised to 8). */
 moe_status_t moe_set_option(const char* name, int value);
 
 #ifdef __cplusplus

@@ -301,6 +301,11 @@ moe_status_t moe_layer_forward(const void* x, const void* w_router, const float*
 }
 
 moe_status_t moe_set_option(const char* name, int value) {
+    if (name && strcmp(name, "gemm_workgroups") == 0) {
+        if (value < 0) return fail(MOE_ERR_INVALID_ARG, "moe_set_option: gemm_workgroups must be >= 0");
+        moe::set_persist_workgroups(value);
+        return MOE_OK;
+    }
     if (name && strcmp(name, "gemm_variant") == 0) {
         g_gemm_variant = value;
         return MOE_OK;

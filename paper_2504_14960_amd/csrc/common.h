@@ -53,6 +53,9 @@ void launch_combine(const void* y_perm, const int32_t* row_of_assign, const floa
                     const void* addend, int T, int H, int K, int r_max, moe_dtype_t dt, void* y,
                     hipStream_t s);
 
+// persistent grouped-GEMM kernels: workgroups per launch, 0 = one per compute unit
+void set_persist_workgroups(int n);
+
 // grouped NT GEMMs of the expert FFN.  phase bit 0: gate/up + SwiGLU (x_perm ->
 // h); bit 1: down projection (h -> y_perm).  Returns false if unsupported.
 bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,

@@ -1,0 +1,567 @@
+// Grouped expert GEMM (a3), persistent kernel: one workgroup per compute unit
+// walks a static list of output tiles and treats their k-tiles as ONE stream.
+//
+// Same tile engine as gemm_pipe3.hip (256 x 256 x 64 tiles, three LDS stages
+// for the activation tile and two for the weight tile, direct global->LDS
+// loads spread in source order between the MFMA groups, one barrier per
+// k-tile).  What changes is what happens at a tile boundary:
+//
+//  * the loads issued during the last two k-tiles of a tile already fetch the
+//    first two k-tiles of the workgroup's NEXT tile, so the pipeline never
+//    drains and there is no per-tile prologue;
+//  * the tile scheduler (prefix of per-expert M-tile counts) lives in registers
+//    of every wave and is evaluated with wave-level operations only: no LDS, no
+//    barrier, no memory access per tile;
+//  * the epilogue goes through the one LDS stage that is idle at that moment:
+//    every wave transposes its accumulators through a private, XOR-swizzled
+//    patch of it and writes whole 16-byte-per-lane row segments, instead of
+//    8-byte pieces scattered over 32 rows per store instruction.
+//
+// The workgroups never wait for one another, so any number of them may be
+// resident; the launcher asks for one per compute unit.
+#include "gemm_tile.h"
+
+namespace moe {
+
+#ifdef MOE_PIPE_TIMING
+// instrumentation build only: per-workgroup, per-wave tick counters
+// {loops, epilogues, whole kernel, tiles, 100 MHz clock over the kernel}
+__device__ unsigned long long g_persist_ticks[1024 * 8 * 8];
+#endif
+
+namespace {
+
+// force a wave-uniform value into scalar registers
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ const uint8_t* uni(const uint8_t* p) {
+    const uint64_t u = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = uni((uint32_t)u), hi = uni((uint32_t)(u >> 32));
+    return reinterpret_cast<const uint8_t*>(((uint64_t)hi << 32) | lo);
+}
+
+// wave-uniform description of one output tile
+struct PTile {
+    const uint8_t* a;   // first activation row of the tile (k = 0)
+    const uint8_t* b0;  // first weight row: gate (SwiGLU) or down projection
+    const uint8_t* b1;  // first up-projection row (SwiGLU only)
+    uint32_t a_lim;     // byte offset (from a) of the last valid activation row
+    uint32_t b_lim;     // byte offset (from b0 / b1) of the last valid weight row
+    int row0, rows, n0;
+    bool valid;
+};
+
+// Every wave keeps the whole schedule in registers: lane l describes experts
+// 4l .. 4l+3 (first row, row count, exclusive prefix of M-tile counts).
+template <int BM>
+struct TileSched {
+    int lo[4], n[4], pex[4], pend;
+    int MT, ntn, per, nwx, wgx, xcd, total;
+
+    __device__ __forceinline__ void init(const int32_t* __restrict__ offsets, int E, int ntn_, int lane) {
+        int mt[4], s = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = lane * 4 + j;
+            lo[j] = 0;
+            n[j] = 0;
+            if (e < E) {
+                lo[j] = offsets[e];
+                n[j] = offsets[e + 1] - lo[j];
+            }
+            mt[j] = (n[j] > 0) ? (n[j] + BM - 1) / BM : 0;
+            s += mt[j];
+        }
+        int incl = s;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += o;
+        }
+        pex[0] = incl - s;
+#pragma unroll
+        for (int j = 1; j < 4; ++j) pex[j] = pex[j - 1] + mt[j - 1];
+        pend = incl;
+        MT = __builtin_amdgcn_readlane(incl, 63);
+        ntn = ntn_;
+        total = MT * ntn;
+        per = (total + 7) / 8;              // tiles per XCD share
+        xcd = blockIdx.x & 7;               // workgroups are dealt round-robin to the 8 XCDs
+        wgx = blockIdx.x >> 3;
+        nwx = (gridDim.x + 7 - xcd) >> 3;   // workgroups of this launch that share the XCD
+    }
+
+    // the i-th tile of this workgroup
+    __device__ __forceinline__ PTile get(int i, const uint8_t* A, const uint8_t* B0, const uint8_t* B1, int N,
+                                         int K, int outn) const {
+        constexpr int MG = 8;
+        PTile t;
+        t.a = A; t.b0 = B0; t.b1 = B1; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0;
+        const int j = wgx + i * nwx;
+        const int L = xcd * per + j;
+        t.valid = (j < per) && (L < total);
+        if (!t.valid) return t;
+        const int qm = L / ntn;
+        int hit = -1, my_p = 0, my_end = 0, my_lo = 0, my_n = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int end = (q < 3) ? pex[q + 1] : pend;
+            if (pex[q] <= qm && qm < end) {
+                hit = q; my_p = pex[q]; my_end = end; my_lo = lo[q]; my_n = n[q];
+            }
+        }
+        const uint64_t bal = __ballot(hit >= 0);  // exactly one lane: the M-tile ranges partition [0, MT)
+        const int src = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)bal) - 1);
+        const int e = 4 * src + __builtin_amdgcn_readlane(hit, src);
+        const int p_e = __builtin_amdgcn_readlane(my_p, src);
+        const int mt_e = __builtin_amdgcn_readlane(my_end, src) - p_e;
+        const int lo_e = __builtin_amdgcn_readlane(my_lo, src);
+        const int n_e = __builtin_amdgcn_readlane(my_n, src);
+        // inside an expert: ceil(mt/MG) groups of near-equal size, tiles ordered
+        // (M-group, N, M-in-group) so that concurrently running tiles share panels in L2
+        const int Le = L - p_e * ntn;
+        const int ng = (mt_e + MG - 1) / MG;
+        const int gbase = mt_e / ng, grem = mt_e % ng;
+        const int big = grem * (gbase + 1) * ntn;
+        int g, gsz, m_first, rem;
+        if (Le < big) {
+            gsz = gbase + 1;
+            g = Le / (gsz * ntn);
+            rem = Le - g * gsz * ntn;
+            m_first = g * gsz;
+        } else {
+            gsz = gbase;
+            g = (Le - big) / (gsz * ntn);
+            rem = (Le - big) - g * gsz * ntn;
+            m_first = grem * (gbase + 1) + g * gsz;
+        }
+        const int nt = rem / gsz;
+        const int m = m_first + rem - nt * gsz;
+        t.row0 = uni(lo_e + m * BM);
+        t.rows = uni(min(BM, lo_e + n_e - t.row0));
+        t.n0 = uni(nt * outn);
+        const size_t k2 = (size_t)K * 2;
+        t.a = uni(A + (size_t)t.row0 * k2);
+        const size_t brow = ((size_t)e * N + t.n0) * k2;
+        t.b0 = uni(B0 + brow);
+        t.b1 = uni(B1 + brow);
+        t.a_lim = uni((uint32_t)(t.rows - 1) * (uint32_t)k2);
+        t.b_lim = uni((uint32_t)(min(outn, N - t.n0) - 1) * (uint32_t)k2);
+        return t;
+    }
+};
+
+// Epilogue through LDS.  For fragment row block i the wave writes its 32 x
+// (32*FO) bf16 outputs (8 bytes per lane per store: row l%32, 4 consecutive
+// columns) into a private patch of W = 64*FO bytes per row, 16-byte granules
+// XOR-swizzled by the row so that neither side has bank conflicts, reads them
+// back as whole 16-byte granules along the rows and stores those.
+template <int FM, int FN, int WM, bool SWIGLU, bool ACC_IN_AGPR>
+__device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_row0, int t_rows, int t_n0,
+                                                  bf16_t* __restrict__ C, int N, int wm, int wn, int lane,
+                                                  uint8_t* stage) {
+    constexpr int FO = SWIGLU ? FN / 2 : FN;
+    constexpr int W = FO * 64;        // bytes per staged row
+    constexpr int GPR = W / 16;       // granules per row
+    constexpr int RP256 = 256 / W;    // rows per 256 bytes (one pass over all banks)
+    constexpr int RPI = 1024 / W;     // rows per 64-lane read
+    static_assert(W <= 256 && 256 % W == 0, "staged row must divide the bank window");
+    // the lane-dependent addresses below are cheap to recompute per tile; hiding
+    // the lane id keeps them from being hoisted out of the tile loop, where they
+    // would occupy registers across the whole k loop
+    asm volatile("" : "+v"(lane));
+    const int fr = lane & 31, fk = lane >> 5;
+    const int xw = (fr / RP256) & (GPR - 1);
+    uint8_t* wrow = stage + fr * W + 8 * fk;
+    const int rl = lane / GPR, gl = lane % GPR;
+    const int col = t_n0 + wn * (FO * 32) + gl * 8;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        // one row block at a time.  With 256 accumulators per lane they live in
+        // the accumulation registers; naming them there once more per block keeps
+        // the copies into ordinary registers from being made all at once, which
+        // would push the loop's long-lived values out to scratch memory
+        __builtin_amdgcn_sched_barrier(0);
+        if (ACC_IN_AGPR) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
+        }
+#pragma unroll
+        for (int j = 0; j < FO; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (SWIGLU) {
+                        const float g = acc[i][j][4 * q + u];
+                        const float up = acc[i][j + FO][4 * q + u];
+                        v[u] = g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * up;  // silu(g) * up
+                    } else {
+                        v[u] = acc[i][j][4 * q + u];
+                    }
+                }
+                u32x2 o;
+                o[0] = pack2_bf16(v[0], v[1]);
+                o[1] = pack2_bf16(v[2], v[3]);
+                *reinterpret_cast<u32x2*>(wrow + (((4 * j + q) ^ xw) << 4)) = o;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int row = it * RPI + rl;
+            const int xr = (row / RP256) & (GPR - 1);
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * W + ((gl ^ xr) << 4));
+            const int grow = wm * WM + i * 32 + row;
+            if (grow < t_rows && col < N)
+                *reinterpret_cast<u32x4*>(C + (size_t)(t_row0 + grow) * N + col) = v;
+        }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
+    const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
+    const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, int ntn) {
+    constexpr int BK = 64;
+    constexpr int NW = WGM * WGN;
+    constexpr int NT = NW * 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int CPR = BK / 8;
+    constexpr int RPP = NT / CPR;               // tile rows fetched per pass of the workgroup
+    constexpr int PA = BM / RPP, PB = BN / RPP;
+    constexpr int ROWB = BK * 2;
+    constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
+    constexpr int B_REGION = 3 * A_BYTES;       // three activation slots, then two weight slots
+    constexpr int OUTN = SWIGLU ? BN / 2 : BN;
+    constexpr int NLOAD = PA + PB;              // direct loads per thread per k-tile (weights first)
+    constexpr int NREAD = FM + FN;
+    constexpr int NMFMA = FM * FN;
+    constexpr int NSLOT = NREAD;
+    constexpr int MPS = NMFMA / NSLOT;
+    // a period's loads are spread over the k-steps 3 (of the previous k-tile), 0 and 1
+    constexpr int LA = NLOAD / 3;
+    constexpr int LB = LA + (NLOAD - LA + 1) / 2;
+    constexpr int LC = NLOAD;
+    constexpr int FO = SWIGLU ? FN / 2 : FN;
+    static_assert(BM % RPP == 0 && BN % RPP == 0 && RPP % 8 == 0, "tile rows must divide into fetch passes");
+    static_assert(!SWIGLU || ((BN / 2) % RPP == 0 && FN % 2 == 0), "gate/up halves must be pass- and fragment-aligned");
+    static_assert(LA <= PB, "only weight loads may be issued under k-step 3");
+    static_assert(LB - LA <= NSLOT && LC - LB <= NSLOT && LA <= NSLOT, "not enough slots for the loads");
+    static_assert(PA < 64, "vmcnt holds 6 bits");
+    static_assert(3 * A_BYTES + 2 * B_BYTES <= 160 * 1024, "tile stages exceed the 160 KiB of LDS");
+    static_assert(NW * 32 * FO * 64 <= A_BYTES, "epilogue patches must fit into one activation slot");
+
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+#ifdef MOE_PIPE_TIMING
+    const unsigned long long tk_entry = __builtin_amdgcn_s_memtime();
+    const unsigned long long rt_entry = __builtin_amdgcn_s_memrealtime();
+    unsigned long long tk_loop = 0, tk_epi = 0, tk_tiles = 0;
+#endif
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    const uint8_t* const Ab = reinterpret_cast<const uint8_t*>(A);
+    const uint8_t* const B0b = reinterpret_cast<const uint8_t*>(B0);
+    const uint8_t* const B1b = SWIGLU ? reinterpret_cast<const uint8_t*>(B1) : B0b;
+
+    TileSched<BM> sched;
+    sched.init(offsets, E, ntn, lane);
+    // current and next tile of this workgroup, as plain wave-uniform scalars
+    int ti = 0;
+    const uint8_t *c_a, *c_b0, *c_b1, *n_a, *n_b0, *n_b1;
+    uint32_t c_alim, c_blim, n_alim, n_blim;
+    int c_row0, c_rows, c_n0, n_row0, n_rows, n_n0;
+    bool n_valid;
+    {
+        const PTile t = sched.get(0, Ab, B0b, B1b, N, K, OUTN);
+        if (!t.valid) return;
+        c_a = t.a; c_b0 = t.b0; c_b1 = t.b1; c_alim = t.a_lim; c_blim = t.b_lim;
+        c_row0 = t.row0; c_rows = t.rows; c_n0 = t.n0;
+    }
+    auto fetch_next_tile = [&](int i) {
+        const PTile t = sched.get(i, Ab, B0b, B1b, N, K, OUTN);
+        n_a = t.a; n_b0 = t.b0; n_b1 = t.b1; n_alim = t.a_lim; n_blim = t.b_lim;
+        n_row0 = t.row0; n_rows = t.rows; n_n0 = t.n0; n_valid = t.valid;
+    };
+    fetch_next_tile(1);
+
+    // global side of the direct loads: thread (frow, fchunk) of a pass fetches
+    // 16 bytes of tile row p*RPP + frow; the chunk it asks for is XOR-swizzled
+    // so that the LDS side can stay linear (lane * 16 bytes)
+    const int frow = tid / CPR, fchunk = tid % CPR;
+    const uint32_t k2 = (uint32_t)K * 2u;
+    const uint32_t vrow = (uint32_t)frow * k2;
+    const uint32_t vswz = (uint32_t)((fchunk ^ (frow & 7)) * 16);
+    const uint32_t step = (uint32_t)RPP * k2;
+    const int wbase = (wave * 64 / CPR) * ROWB;
+
+    auto fetch_a = [&](int p, const uint8_t* base, uint32_t lim, uint8_t* st) {
+        const uint32_t off = min(vrow + (uint32_t)p * step, lim) + vswz;  // ragged tail: a valid row again
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + off),
+                                         (__attribute__((address_space(3))) void*)(st + p * RPP * ROWB + wbase), 16,
+                                         0, 0);
+    };
+    auto fetch_b = [&](int p, const uint8_t* base0, const uint8_t* base1, uint32_t lim, uint8_t* st) {
+        const int pp = SWIGLU ? p % (PB / 2) : p;
+        const uint8_t* base = (SWIGLU && p >= PB / 2) ? base1 : base0;
+        const uint32_t off = min(vrow + (uint32_t)pp * step, lim) + vswz;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + off),
+                                         (__attribute__((address_space(3))) void*)(st + p * RPP * ROWB + wbase), 16,
+                                         0, 0);
+    };
+    // where k-tile kk of the stream that starts at cur's k-tile 0 comes from
+    struct Src {
+        const uint8_t* a;
+        const uint8_t* b0;
+        const uint8_t* b1;
+        uint32_t a_lim, b_lim;
+    };
+    const int KT = K / BK;
+    auto src = [&](int kk) -> Src {
+        const bool in_cur = kk < KT;
+        const bool use_cur = in_cur || !n_valid;  // past the last tile: its last k-tile again, never used
+        const int k = in_cur ? kk : (n_valid ? kk - KT : KT - 1);
+        const size_t kbyte = (size_t)k * (BK * 2);
+        Src s;
+        s.a = (use_cur ? c_a : n_a) + kbyte;
+        s.b0 = (use_cur ? c_b0 : n_b0) + kbyte;
+        s.b1 = (use_cur ? c_b1 : n_b1) + kbyte;
+        s.a_lim = use_cur ? c_alim : n_alim;
+        s.b_lim = use_cur ? c_blim : n_blim;
+        return s;
+    };
+    // load i of a period: i < PB -> pass i of the weight tile (source se, slot
+    // ld_b), else pass i - PB of the activation tile (source sl, slot ld_a)
+    auto fetch_one = [&](int i, const Src& se, const Src& sl, uint8_t* ld_b, uint8_t* ld_a) {
+        if (i < PB)
+            fetch_b(i, se.b0, se.b1, se.b_lim, ld_b);
+        else
+            fetch_a(i - PB, sl.a, sl.a_lim, ld_a);
+    };
+
+    const int fr = lane & 31, fk = lane >> 5;
+    int a_off[FM], b_off[FN];
+    const int f_sw = fr & 7;  // every fragment row is fr mod 8 (fragments start at multiples of 32)
+#pragma unroll
+    for (int i = 0; i < FM; ++i) a_off[i] = (wm * WM + i * 32 + fr) * ROWB;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        int r;
+        if (SWIGLU) {
+            constexpr int half = FN / 2;
+            r = (j < half) ? (wn * (WN / 2) + j * 32 + fr) : (BN / 2 + wn * (WN / 2) + (j - half) * 32 + fr);
+        } else {
+            r = wn * WN + j * 32 + fr;
+        }
+        b_off[j] = r * ROWB;
+    }
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    bf16x8 af[2][FM], bfg[2][FN];
+    auto read_one = [&](const uint8_t* sa, const uint8_t* sb, int s, int buf, int q) {
+        const int c = ((2 * s + fk) ^ f_sw) << 4;
+        if (q < FM)
+            af[buf][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sa + a_off[q] + c));
+        else
+            bfg[buf][q - FM] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sb + b_off[q - FM] + c));
+    };
+    auto mfma_one = [&](int buf, int m) {
+        const int i = m / FN, j = m % FN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfg[buf][j], af[buf][i], acc[i][j], 0, 0, 0);
+    };
+    // one k-step in issue order: NSLOT slots of {MPS MFMAs on set mf_buf; up to
+    // 2 fragment reads of k-step rd_s into the other set; one direct load}
+    auto kstep = [&](int mf_buf, const uint8_t* rd_a, const uint8_t* rd_b, int rd_s, int ld_begin, int ld_end,
+                     const Src& se, const Src& sl, uint8_t* ld_b, uint8_t* ld_a) {
+        int m = 0, rd = 0, ld = ld_begin;
+#pragma unroll
+        for (int slot = 0; slot < NSLOT; ++slot) {
+#pragma unroll
+            for (int q = 0; q < MPS; ++q) {
+                mfma_one(mf_buf, m);
+                ++m;
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                if (rd < NREAD) {
+                    read_one(rd_a, rd_b, rd_s, mf_buf ^ 1, rd);
+                    ++rd;
+                }
+            if (ld < ld_end) {
+                fetch_one(ld, se, sl, ld_b, ld_a);
+                ++ld;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int mm = NSLOT * MPS; mm < NMFMA; ++mm) mfma_one(mf_buf, mm);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    uint8_t* const a_region = smem;
+    uint8_t* const b_region = smem + B_REGION;
+
+    // prologue (first tile of this workgroup only): A(0), B(0), then A(1); only
+    // the first two must have landed before the first fragment reads
+    {
+        const Src s0 = src(0), s1 = src(1);
+#pragma unroll
+        for (int i = PB; i < NLOAD; ++i) fetch_one(i, s0, s0, b_region, a_region);
+#pragma unroll
+        for (int i = 0; i < PB; ++i) fetch_one(i, s0, s0, b_region, a_region);
+#pragma unroll
+        for (int i = PB; i < NLOAD; ++i) fetch_one(i, s1, s1, b_region, a_region + A_BYTES);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (PA & 0xF) | ((PA >> 4) << 14));  // vmcnt(PA)
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int q = 0; q < NREAD; ++q) read_one(a_region, b_region, 0, 0, q);
+        // head of B(1) into weight slot 1
+#pragma unroll
+        for (int i = 0; i < LA; ++i) fetch_one(i, s1, s1, b_region + B_BYTES, a_region);
+    }
+
+    int l0 = 0, l1 = A_BYTES, l2 = 2 * A_BYTES;  // activation slots of k-tiles kt, kt+1, kt+2
+    int e0 = 0, e1 = B_BYTES;                    // weight slots of k-tiles kt, kt+1
+    for (;;) {
+#ifdef MOE_PIPE_TIMING
+        const unsigned long long tk_l0 = __builtin_amdgcn_s_memtime();
+#endif
+        for (int kt = 0; kt < KT; ++kt) {
+            const Src s1 = src(kt + 1), s2 = src(kt + 2);
+            const uint8_t* ca = a_region + l0;
+            const uint8_t* cb = b_region + e0;
+            uint8_t* lb = b_region + e1;  // B(kt+1)
+            uint8_t* la = a_region + l2;  // A(kt+2)
+            __builtin_amdgcn_sched_barrier(0);
+            kstep(0, ca, cb, 1, LA, LB, s1, s2, lb, la);  // k-step 0
+            kstep(1, ca, cb, 2, LB, LC, s1, s2, lb, la);  // k-step 1
+            kstep(0, ca, cb, 3, LC, LC, s1, s2, lb, la);  // k-step 2
+            // B(kt+1) was issued before A(kt+2) in this period and A(kt+1) a period
+            // ago: all but the PA youngest loads must have landed; this wave's
+            // fragment reads of k-tile kt are in registers (lgkmcnt(0))
+            __builtin_amdgcn_s_waitcnt((PA & 0xF) | ((PA >> 4) << 14));
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // k-step 3: first fragments of k-tile kt+1; the weight slot of k-tile
+            // kt is free, the head of B(kt+2) goes into it
+            kstep(1, a_region + l1, b_region + e1, 0, 0, LA, s2, s2, b_region + e0, a_region);
+            const int tl = l0;
+            l0 = l1;
+            l1 = l2;
+            l2 = tl;
+            const int te = e0;
+            e0 = e1;
+            e1 = te;
+        }
+#ifdef MOE_PIPE_TIMING
+        const unsigned long long tk_l1 = __builtin_amdgcn_s_memtime();
+#endif
+        // Epilogue.  The activation slot that held the last k-tile (now l2) is
+        // idle: every wave finished reading it before the last barrier, and the
+        // next loads into it are issued only after the barrier below.
+        store_tile_staged<FM, FN, WM, SWIGLU, (FM * FN * 16 > 128)>(acc, c_row0, c_rows, c_n0, C, N, wm, wn, lane,
+                                              a_region + l2 + wave * (32 * FO * 64));
+        if (!n_valid) break;
+        c_a = n_a; c_b0 = n_b0; c_b1 = n_b1; c_alim = n_alim; c_blim = n_blim;
+        c_row0 = n_row0; c_rows = n_rows; c_n0 = n_n0;
+        ++ti;
+        fetch_next_tile(ti + 1);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave is done with its patch
+        __builtin_amdgcn_s_barrier();
+#ifdef MOE_PIPE_TIMING
+        tk_loop += tk_l1 - tk_l0;
+        tk_epi += __builtin_amdgcn_s_memtime() - tk_l1;
+        ++tk_tiles;
+#endif
+    }
+    wait_vmcnt0();  // loads past the end of the last tile may still be landing in LDS
+#ifdef MOE_PIPE_TIMING
+    if (lane == 0 && blockIdx.x < 1024) {
+        unsigned long long* o = g_persist_ticks + ((size_t)blockIdx.x * 8 + wave) * 8;
+        o[0] = tk_loop;
+        o[1] = tk_epi;
+        o[2] = __builtin_amdgcn_s_memtime() - tk_entry;
+        o[3] = tk_tiles;
+        o[4] = __builtin_amdgcn_s_memrealtime() - rt_entry;
+    }
+#endif
+}
+
+int g_persist_workgroups = 0;  // 0: one per compute unit
+
+int persist_grid() {
+    // every one of the 8 tile shares needs a workgroup with its residue mod 8
+    if (g_persist_workgroups > 0) return g_persist_workgroups < 8 ? 8 : g_persist_workgroups;
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus < 8) cus = 256;
+    }
+    return cus;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B0,
+                    const void* B1, void* C, hipStream_t s) {
+    constexpr int OUTN = SWIGLU ? BN / 2 : BN;
+    constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
+    const int ntn = (N + OUTN - 1) / OUTN;
+    auto kern = gemm_bf16_persist_kernel<BM, BN, WGM, WGN, SWIGLU>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)smem);
+        attr_set = true;
+    }
+    // never more workgroups than the static bound on the tile count
+    const int grid = min(persist_grid(), grid_for(r_max, E, BM, ntn));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A), offsets, E, N,
+                       K, static_cast<const bf16_t*>(B0), static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C),
+                       ntn);
+}
+
+template <int BM, int BN, int WGM, int WGN>
+void run_persist_pair(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                      const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm, int phase,
+                      hipStream_t s) {
+    if (phase & 1) launch_persist<BM, BN, WGM, WGN, true>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, s);
+    if (phase & 2) launch_persist<BM, BN, WGM, WGN, false>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
+}
+
+}  // namespace
+
+void set_persist_workgroups(int n) { g_persist_workgroups = n; }
+
+bool launch_persist_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                        const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm,
+                        int variant, int phase, hipStream_t s) {
+    if (H < 128 || F < 128) return false;  // the k stream needs at least two k-tiles per output tile
+    switch (variant) {
+        case 40: run_persist_pair<256, 256, 2, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 41: run_persist_pair<256, 256, 2, 4>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        default: return false;
+    }
+}
+
+}  // namespace moe

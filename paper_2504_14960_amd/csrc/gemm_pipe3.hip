@@ -20,8 +20,9 @@
 namespace moe {
 
 #ifdef MOE_PIPE_TIMING
-// instrumentation build only: per-wave tick counters {loop, load wait, barrier wait}
-__device__ unsigned long long g_pipe3_ticks[4096 * 8 * 4];
+// instrumentation build only: per-wave tick counters {loop, load wait, barrier
+// wait, loop begin, kernel entry, kernel exit, 100 MHz clock at loop begin / end}
+__device__ unsigned long long g_pipe3_ticks[8192 * 8 * 8];
 #endif
 
 namespace {
@@ -70,6 +71,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     static_assert(A_SLOTS * A_BYTES + B_SLOTS * B_BYTES <= 160 * 1024, "tile stages exceed the 160 KiB of LDS");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+#ifdef MOE_PIPE_TIMING
+    const unsigned long long tk_entry = __builtin_amdgcn_s_memtime();
+#endif
     // the tile scheduler's scratch lives in the second weight slot, which is not
     // written before the prologue's barrier
     int* sched = reinterpret_cast<int*>(smem + (TRI_B ? A_BYTES : B_REGION + B_BYTES));  // second early slot
@@ -223,6 +227,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
 #ifdef MOE_PIPE_TIMING
     unsigned long long tk_wait = 0, tk_bar = 0;
     const unsigned long long tk_begin = __builtin_amdgcn_s_memtime();
+    const unsigned long long rt_begin = __builtin_amdgcn_s_memrealtime();
 #endif
     for (int kt = 0; kt < KT; ++kt) {
         const uint8_t* ca = a_ptr(e0, l0);
@@ -262,16 +267,25 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
         e1 = te;
     }
 #ifdef MOE_PIPE_TIMING
-    if (lane == 0 && blockIdx.x < 4096) {
-        unsigned long long* o = g_pipe3_ticks + ((size_t)blockIdx.x * 8 + wave) * 4;
-        o[0] = __builtin_amdgcn_s_memtime() - tk_begin;
-        o[1] = tk_wait;
-        o[2] = tk_bar;
-        o[3] = tk_begin;
-    }
+    const unsigned long long tk_end = __builtin_amdgcn_s_memtime();
+    const unsigned long long rt_end = __builtin_amdgcn_s_memrealtime();
 #endif
     wait_vmcnt0();  // loads past the end of K may still be landing in LDS
     store_tile<FM, FN, WM, WN, BN, SWIGLU>(acc, tile, C, N, n0, wm, wn, lane);
+#ifdef MOE_PIPE_TIMING
+    wait_vmcnt0();
+    if (lane == 0 && blockIdx.x < 8192) {
+        unsigned long long* o = g_pipe3_ticks + ((size_t)blockIdx.x * 8 + wave) * 8;
+        o[0] = tk_end - tk_begin;
+        o[1] = tk_wait;
+        o[2] = tk_bar;
+        o[3] = tk_begin;
+        o[4] = tk_entry;
+        o[5] = __builtin_amdgcn_s_memtime();
+        o[6] = rt_begin;
+        o[7] = rt_end;
+    }
+#endif
 }
 
 template <int BM, int BN, int WGM, int WGN, bool SWIGLU, int DIST, bool TRI_B>

@@ -174,4 +174,9 @@ bool launch_pipe3_ffn(const void* x_perm, const int32_t* offsets, int r_max, int
                       const void* w_gate, const void* w_up, const void* w_down, void* h,
                       void* y_perm, int variant, int phase, hipStream_t s);
 
+// persistent kernels, one workgroup per compute unit (gemm_persist.hip)
+bool launch_persist_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                        const void* w_gate, const void* w_up, const void* w_down, void* h,
+                        void* y_perm, int variant, int phase, hipStream_t s);
+
 }  // namespace moe

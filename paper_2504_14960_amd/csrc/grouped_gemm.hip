@@ -353,13 +353,18 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
         return true;
     }
     if (variant == 0) {
-        // tuned defaults (Mixtral-8x22B layer shape on MI355X): the kernels with three
-        // activation stages, 8 waves for the gate/up GEMM, 4 waves for the down projection
+        // tuned default (Mixtral-8x22B layer shape on MI355X): the persistent 8-wave
+        // kernel for both GEMMs; layers too shallow for its k stream fall back to the
+        // kernels with three activation stages (8 waves gate/up, 4 waves down)
+        if (launch_persist_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 41, phase, s))
+            return true;
         bool ok = true;
         if (phase & 1) ok = ok && launch_pipe3_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 31, 1, s);
         if (phase & 2) ok = ok && launch_pipe3_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 30, 2, s);
         return ok;
     }
+    if (variant >= 40 && launch_persist_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, variant, phase, s))
+        return true;
     if (variant >= 30 && launch_pipe3_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, variant, phase, s))
         return true;
     if (variant >= 10 && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, variant, phase, s))

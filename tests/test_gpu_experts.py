@@ -8,7 +8,7 @@ from helpers import assert_close, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
-ALL_VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 12, 13, 14, 15, 16, 17, 20, 21, 22, 23, 30, 31, 32, 33, 34, 35, 99]
+ALL_VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 12, 13, 14, 15, 16, 17, 20, 21, 22, 23, 30, 31, 32, 33, 34, 35, 40, 41, 99]
 
 
 def _offsets(counts):
@@ -58,7 +58,7 @@ def test_every_kernel_variant_on_ragged_experts(ragged_case, variant):
     assert_close(y, y_ref, True, f"y_perm (variant {variant})")
 
 
-@pytest.mark.parametrize("variant", [0, 12, 20, 21, 30, 31])
+@pytest.mark.parametrize("variant", [0, 12, 20, 21, 30, 31, 40, 41])
 def test_deep_contraction_and_fine_grained_experts(variant):
     # long K loops (many k-tiles) and many small experts
     inp, x_perm, offsets, h_ref, y_ref = _case(H=1536, F=128, E=3, counts=[130, 257, 40], seed=4100)
@@ -73,13 +73,29 @@ def test_deep_contraction_and_fine_grained_experts(variant):
     assert_close(y, y_ref, True, "y fine-grained")
 
 
-@pytest.mark.parametrize("variant", [0, 5, 20, 30, 31])
+@pytest.mark.parametrize("variant", [0, 5, 20, 30, 31, 40, 41])
 def test_experts_with_more_m_tiles_than_one_scheduler_group(variant):
     # 2400 rows = 10 (or 19) M-tiles: the scheduler cuts them into balanced groups
     inp, x_perm, offsets, h_ref, y_ref = _case(H=128, F=128, E=3, counts=[2400, 130, 4500], seed=4150)
     h, y = _run(x_perm, offsets, inp, variant)
     assert_close(h, h_ref, True, "h many tiles")
     assert_close(y, y_ref, True, "y many tiles")
+
+
+@pytest.mark.parametrize("variant", [40, 41])
+@pytest.mark.parametrize("workgroups", [8, 24, 13])
+def test_persistent_kernel_walks_many_tiles_per_workgroup(ragged_case, variant, workgroups):
+    # few workgroups => each one streams through several tiles (tile boundaries,
+    # ragged tails and the end of its list all inside one kernel instance)
+    import paper_2504_14960_amd as moe
+    inp, x_perm, offsets, h_ref, y_ref = ragged_case
+    moe.set_option("gemm_workgroups", workgroups)
+    try:
+        h, y = _run(x_perm, offsets, inp, variant)
+    finally:
+        moe.set_option("gemm_workgroups", 0)
+    assert_close(h, h_ref, True, f"h (variant {variant}, {workgroups} workgroups)")
+    assert_close(y, y_ref, True, f"y_perm (variant {variant}, {workgroups} workgroups)")
 
 
 def test_rows_past_the_last_expert_are_untouched_and_result_is_reproducible():
