@@ -124,73 +124,127 @@ __device__ __forceinline__ void select_dispatch(const float* rows, int ld, int n
         select_block<4>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
 }
 
-// Selection with one LANE per token (K <= KSEL <= 8): the lane walks its
-// token's E logits once, keeping the KSEL best in a sorted register list
-// (insertion by compare-and-swap, so equal logits keep the lower index first),
-// then a second walk for the softmax denominator.  No cross-lane traffic at
-// all, which beats the butterfly version by a wide margin for E = 64: that one
-// spends its time waiting on chains of dependent cross-lane permutes.
-// `rows` must be LDS (row stride `ld`, odd => conflict-free); thread i of the
-// workgroup handles token i.
-template <int KSEL>
+// Selection with L lanes per token (K <= KSEL <= 8, L in {1, 2, 4, 8}).  Lane
+// `sub` of a token walks its block of ceil(E/L) consecutive logits (with an odd
+// row stride the lanes of a wave then hit distinct LDS banks), keeping its KSEL
+// best in a sorted register list (insertion by compare-and-swap on the key
+// (value desc, index asc), so equal logits keep the lower index first).  The L
+// lists are then merged pairwise across lanes: the element-wise better of my
+// list and the partner's reversed list is a bitonic sequence holding the KSEL
+// best of both, and log2(KSEL) compare-exchange stages sort it; both partners
+// end with the same list.  A second walk gives the softmax denominator.
+// L = 1 needs no cross-lane traffic at all; L = 8 gives 8192 tokens of a
+// 64-expert layer 1024 waves of work instead of 128.
+// `rows` must be LDS (row stride `ld`, odd => conflict-free).
+template <int KSEL, int L>
 __device__ __forceinline__ void select_lanes(const float* rows, int ld, int ntok, int t0, int T, int E,
                                              int K, int renorm, int32_t* topk_idx, float* topk_gate) {
-    const int lt = threadIdx.x;
-    if (lt >= ntok || t0 + lt >= T) return;
-    const float* r = rows + (size_t)lt * ld;
-    float lv[KSEL];
-    int le[KSEL];
-#pragma unroll
-    for (int j = 0; j < KSEL; ++j) {
-        lv[j] = -INFINITY;
-        le[j] = 0x7fffffff;
-    }
-    for (int e = 0; e < E; ++e) {
-        float cv = r[e];
-        cv = (cv != cv) ? -INFINITY : cv;  // NaN ranks last
-        int ce = e;
+    const int sub = threadIdx.x % L;
+    const int tpb = blockDim.x / L;  // tokens per pass of the workgroup
+    for (int base = 0; base < ntok; base += tpb) {
+        const int lt = base + threadIdx.x / L;
+        const bool valid = lt < ntok && t0 + lt < T;  // same for the L lanes of a token
+        const float* r = rows + (size_t)(valid ? lt : 0) * ld;
+        float lv[KSEL];
+        int le[KSEL];
 #pragma unroll
         for (int j = 0; j < KSEL; ++j) {
-            const bool b = ranks_before(cv, ce, lv[j], le[j]);
-            const float tv = b ? lv[j] : cv;
-            const int te = b ? le[j] : ce;
-            lv[j] = b ? cv : lv[j];
-            le[j] = b ? ce : le[j];
-            cv = tv;
-            ce = te;
+            lv[j] = -INFINITY;
+            le[j] = 0x7fffffff;
         }
-    }
-    const float m = lv[0];
-    float z = 0.f;
-    for (int e = 0; e < E; ++e) {
-        float v = r[e];
-        v = (v != v) ? -INFINITY : v;
-        z += expf(v - m);
-    }
-    float p[KSEL], gsum = 0.f;
+        const int e_begin = sub * ((E + L - 1) / L), e_end = min(E, e_begin + (E + L - 1) / L);
+        for (int e = e_begin; e < e_end; ++e) {
+            float cv = r[e];
+            cv = (cv != cv) ? -INFINITY : cv;  // NaN ranks last
+            int ce = e;
 #pragma unroll
-    for (int k = 0; k < KSEL; ++k) {
-        p[k] = expf(lv[k] - m) / z;
-        if (k < K) gsum += p[k];
-    }
-    const size_t o = (size_t)(t0 + lt) * K;
-#pragma unroll
-    for (int k = 0; k < KSEL; ++k)
-        if (k < K) {
-            topk_idx[o + k] = le[k];
-            topk_gate[o + k] = renorm ? p[k] / gsum : p[k];
+            for (int j = 0; j < KSEL; ++j) {
+                const bool b = ranks_before(cv, ce, lv[j], le[j]);
+                const float tv = b ? lv[j] : cv;
+                const int te = b ? le[j] : ce;
+                lv[j] = b ? cv : lv[j];
+                le[j] = b ? ce : le[j];
+                cv = tv;
+                ce = te;
+            }
         }
+#pragma unroll
+        for (int off = 1; off < L; off <<= 1) {
+            float pv[KSEL];
+            int pe[KSEL];
+#pragma unroll
+            for (int j = 0; j < KSEL; ++j) {
+                pv[j] = __shfl_xor(lv[j], off, 64);
+                pe[j] = __shfl_xor(le[j], off, 64);
+            }
+#pragma unroll
+            for (int j = 0; j < KSEL; ++j) {
+                const bool b = ranks_before(pv[KSEL - 1 - j], pe[KSEL - 1 - j], lv[j], le[j]);
+                lv[j] = b ? pv[KSEL - 1 - j] : lv[j];
+                le[j] = b ? pe[KSEL - 1 - j] : le[j];
+            }
+#pragma unroll
+            for (int d = KSEL / 2; d > 0; d >>= 1)
+#pragma unroll
+                for (int j = 0; j < KSEL; ++j)
+                    if ((j & d) == 0) {
+                        const bool b = ranks_before(lv[j + d], le[j + d], lv[j], le[j]);
+                        const float tv = lv[j];
+                        const int te = le[j];
+                        lv[j] = b ? lv[j + d] : tv;
+                        le[j] = b ? le[j + d] : te;
+                        lv[j + d] = b ? tv : lv[j + d];
+                        le[j + d] = b ? te : le[j + d];
+                    }
+        }
+        const float m = lv[0];
+        float z = 0.f;
+        for (int e = e_begin; e < e_end; ++e) {
+            float v = r[e];
+            v = (v != v) ? -INFINITY : v;
+            z += expf(v - m);
+        }
+#pragma unroll
+        for (int off = 1; off < L; off <<= 1) z += __shfl_xor(z, off, 64);
+        float gsum = 0.f;
+#pragma unroll
+        for (int k = 0; k < KSEL; ++k)
+            if (k < K) gsum += expf(lv[k] - m) / z;
+        // lane `sub` writes the slots sub, sub + L, ...
+#pragma unroll
+        for (int k = 0; k < KSEL; ++k)
+            if (k < K && (k % L) == sub && valid) {
+                const size_t o = (size_t)(t0 + lt) * K;
+                const float p = expf(lv[k] - m) / z;
+                topk_idx[o + k] = le[k];
+                topk_gate[o + k] = renorm ? p / gsum : p;
+            }
+    }
 }
 
-// K <= 8: one lane per token; larger K: one lane group per token.
+// lanes per token of the register-list selection: about 8 logits per lane
+__host__ __device__ inline int lanes_per_token(int E) { return E >= 64 ? 8 : E >= 32 ? 4 : E >= 16 ? 2 : 1; }
+
+template <int KSEL>
+__device__ __forceinline__ void select_lanes_for(const float* rows, int ld, int ntok, int t0, int T, int E,
+                                                 int K, int renorm, int32_t* topk_idx, float* topk_gate) {
+    switch (lanes_per_token(E)) {
+        case 8: select_lanes<KSEL, 8>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate); break;
+        case 4: select_lanes<KSEL, 4>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate); break;
+        case 2: select_lanes<KSEL, 2>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate); break;
+        default: select_lanes<KSEL, 1>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate); break;
+    }
+}
+
+// K <= 8: register lists; larger K: one lane group per token.
 __device__ __forceinline__ void select_tokens(const float* rows, int ld, int ntok, int t0, int T, int E,
                                               int K, int renorm, int32_t* topk_idx, float* topk_gate) {
     if (K <= 2)
-        select_lanes<2>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+        select_lanes_for<2>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
     else if (K <= 4)
-        select_lanes<4>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+        select_lanes_for<4>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
     else if (K <= 8)
-        select_lanes<8>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
+        select_lanes_for<8>(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
     else
         select_dispatch(rows, ld, ntok, t0, T, E, K, renorm, topk_idx, topk_gate);
 }
@@ -343,17 +397,24 @@ __global__ __launch_bounds__(256) void router_f32_kernel(
 }
 
 // ------------------------------------------------------------------ selection only
+constexpr int kTopkTileFloats = 12288;
+
+// tokens per tile of the selection-only kernel: one pass of the workgroup
+__host__ __device__ inline int topk_tile_tokens(int E, int K) {
+    if (K <= 8) return 256 / lanes_per_token(E);
+    const int fit = kTopkTileFloats / (E | 1);
+    return fit > 256 ? 256 : fit;
+}
+
 __global__ __launch_bounds__(256) void topk_only_kernel(const float* __restrict__ logits, int T,
                                                         int E, int K, int renorm,
                                                         int32_t* __restrict__ topk_idx,
                                                         float* __restrict__ topk_gate) {
     // a tile of tokens is copied to LDS with coalesced loads (row stride odd),
     // then selected from there
-    constexpr int kTileFloats = 12288;
-    __shared__ float tile[kTileFloats];
+    __shared__ float tile[kTopkTileFloats];
     const int ld = E | 1;
-    int per_block = kTileFloats / ld;
-    if (per_block > 256) per_block = 256;
+    const int per_block = topk_tile_tokens(E, K);
     for (int t0 = blockIdx.x * per_block; t0 < T; t0 += gridDim.x * per_block) {
         const int ntok = min(per_block, T - t0);
         const float* src = logits + (size_t)t0 * E;
@@ -382,8 +443,7 @@ void launch_router(const void* x, const void* w, const float* bias, float* logit
                    int E, int K, int renorm, moe_dtype_t dt, int32_t* idx, float* gate,
                    hipStream_t s) {
     if (x == nullptr) {
-        int per_block = 12288 / (E | 1);
-        if (per_block > 256) per_block = 256;
+        const int per_block = topk_tile_tokens(E, K);
         int grid = (T + per_block - 1) / per_block;
         if (grid > 4096) grid = 4096;
         hipLaunchKernelGGL(topk_only_kernel, dim3(grid), dim3(256), 0, s, logits, T, E, K, renorm, idx, gate);

@@ -83,7 +83,7 @@ def test_experts_with_more_m_tiles_than_one_scheduler_group(variant):
 
 
 @pytest.mark.parametrize("variant", [40, 41])
-@pytest.mark.parametrize("workgroups", [8, 24, 13])
+@pytest.mark.parametrize("workgroups", [8, 24, 13, 64])
 def test_persistent_kernel_walks_many_tiles_per_workgroup(ragged_case, variant, workgroups):
     # few workgroups => each one streams through several tiles (tile boundaries,
     # ragged tails and the end of its list all inside one kernel instance)
