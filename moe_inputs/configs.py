@@ -1,4 +1,5 @@
-"""The five layer shapes the hot path is exercised on.
+"""The layer shapes the hot path is exercised on: the five benchmark
+configurations, then two more of the paper's models as further workloads.
 
 The paper names the models (Section 4.1, "Models") but not their layer
 dimensions; the dimensions, token counts, top-k and skew recipes here are the
@@ -54,6 +55,18 @@ CONFIGS = {
     "tokendrop": LayerConfig("tokendrop", T=32768, H=4096, E=64, K=6, F=1408,
                              dtype="bf16", renormalize=False, seed=1005,
                              capacity_factor=1.0, bias="zipf1.2"),
+    # Further workloads for the same kernels (Section 4.1, "Models").
+    # Mixtral-8x22B-G8T8, the paper's fine-grained re-parameterisation: every expert
+    # of Mixtral-8x22B cut into 8 (64 experts of one eighth the FFN size, 8 active);
+    # run the way the paper benchmarks, token-drop with capacity factor 1, on a
+    # skewed router.
+    "mixtral8x22b_g8t8": LayerConfig("mixtral8x22b_g8t8", T=8192, H=6144, E=64, K=8, F=2048,
+                                     dtype="bf16", renormalize=True, seed=1006,
+                                     capacity_factor=1.0, bias="normal"),
+    # Llama3-8x70B: 8 experts upcycled from the dense 70B model, 2 active.  The paper
+    # names the model only; hidden and FFN sizes are those of the public 70B model.
+    "llama3_8x70b": LayerConfig("llama3_8x70b", T=8192, H=8192, E=8, K=2, F=28672,
+                                dtype="bf16", renormalize=True, seed=1007),
 }
 
 

@@ -58,7 +58,8 @@ def _run_stages(inp, capacity):
     return o, r_max
 
 
-@pytest.mark.parametrize("name", ["mixtral8x22b", "mixtral8x7b", "qwen2_57b_a14b", "tokendrop"])
+@pytest.mark.parametrize("name", ["mixtral8x22b", "mixtral8x7b", "qwen2_57b_a14b", "tokendrop",
+                                  "mixtral8x22b_g8t8", "llama3_8x70b"])
 def test_full_size_layer(name):
     cfg = get_config(name)
     T, H, E, K, F = cfg.T, cfg.H, cfg.E, cfg.K, cfg.F
