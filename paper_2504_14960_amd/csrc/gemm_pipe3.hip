@@ -14,20 +14,17 @@
 // Everything else (XOR-swizzled 128-byte LDS rows, 32x32x16 bf16 MFMA with
 // the weight fragment first, fragment double buffering, source-ordered
 // interleave frozen by scheduling barriers, ragged tile scheduler, fused
-// SwiGLU epilogue) is as in gemm_pipe.hip.
+// SwiGLU epilogue) is shared with the persistent kernel in gemm_persist.hip,
+// which is this engine without the per-tile prologue and with a coalesced
+// epilogue; this file is the one-workgroup-per-tile form of it.
 #include "gemm_tile.h"
 
 namespace moe {
 
-#ifdef MOE_PIPE_TIMING
-// instrumentation build only: per-wave tick counters {loop, load wait, barrier
-// wait, loop begin, kernel entry, kernel exit, 100 MHz clock at loop begin / end}
-__device__ unsigned long long g_pipe3_ticks[8192 * 8 * 8];
-#endif
 
 namespace {
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU, int DIST, bool TRI_B = false>
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, int ntn) {
@@ -40,28 +37,26 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     constexpr int PA = BM / RPP, PB = BN / RPP;
     constexpr int ROWB = BK * 2;
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
-    // TRI_B = false: three activation slots + two weight slots (the weight tile
-    // is the "early" operand that must be complete at the barrier);
-    // TRI_B = true: the roles are swapped
-    constexpr int A_SLOTS = TRI_B ? 2 : 3, B_SLOTS = TRI_B ? 3 : 2;
+    // three activation slots (the "late" operand, fetched two k-tiles ahead) and
+    // two weight slots (the "early" operand that must be complete at the barrier)
+    constexpr bool TRI_B = false;                // true would swap the roles of the operands
+    constexpr int A_SLOTS = 3, B_SLOTS = 2;
     constexpr int B_REGION = A_SLOTS * A_BYTES;  // B slots start after the A slots
-    constexpr int PE = TRI_B ? PA : PB;          // passes of the early (2-slot) operand
-    constexpr int PL = TRI_B ? PB : PA;          // passes of the late (3-slot) operand
-    constexpr int E_BYTES = TRI_B ? A_BYTES : B_BYTES, L_BYTES = TRI_B ? B_BYTES : A_BYTES;
+    constexpr int PE = PB;                       // passes of the early (2-slot) operand
+    constexpr int PL = PA;                       // passes of the late (3-slot) operand
+    constexpr int E_BYTES = B_BYTES, L_BYTES = A_BYTES;
     constexpr int OUTN = SWIGLU ? BN / 2 : BN;
     constexpr int NLOAD = PA + PB;             // direct loads per thread per period
     constexpr int NREAD = FM + FN;
     constexpr int NMFMA = FM * FN;
     constexpr int NSLOT = NREAD;
     constexpr int MPS = NMFMA / NSLOT;
-    // how a period's NLOAD loads (weight tile first) are spread over the k-steps
-    // 3 (of the previous tile), 0, 1, 2:
-    //   DIST 0: thirds under k-steps 3, 0, 1, one per slot
-    //   DIST 1: quarters under all four k-steps, evenly spaced slots
-    constexpr int LA = (DIST == 1) ? NLOAD / 4 : NLOAD / 3;                     // under k-step 3 (previous tile)
-    constexpr int LB = (DIST == 1) ? NLOAD / 2 : LA + (NLOAD - LA + 1) / 2;     // end of k-step 0's share
-    constexpr int LC = (DIST == 1) ? 3 * NLOAD / 4 : NLOAD;                     // end of k-step 1's share
-    constexpr int LSTRIDE = (DIST == 1) ? NSLOT / ((NLOAD + 3) / 4) : 1;        // slots between two loads
+    // a period's NLOAD loads (weight tile first) go in thirds under the k-steps
+    // 3 (of the previous tile), 0 and 1, one per slot
+    constexpr int LA = NLOAD / 3;                  // under k-step 3 (previous tile)
+    constexpr int LB = LA + (NLOAD - LA + 1) / 2;  // end of k-step 0's share
+    constexpr int LC = NLOAD;                      // end of k-step 1's share
+    constexpr int LSTRIDE = 1;                     // slots between two loads
     static_assert(BM % RPP == 0 && BN % RPP == 0, "tile rows must divide into fetch passes");
     static_assert(!SWIGLU || ((BN / 2) % RPP == 0 && FN % 2 == 0), "gate/up halves must be pass- and fragment-aligned");
     static_assert(LA <= PE, "only early-operand loads may be issued under k-step 3");
@@ -71,9 +66,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     static_assert(A_SLOTS * A_BYTES + B_SLOTS * B_BYTES <= 160 * 1024, "tile stages exceed the 160 KiB of LDS");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-#ifdef MOE_PIPE_TIMING
-    const unsigned long long tk_entry = __builtin_amdgcn_s_memtime();
-#endif
     // the tile scheduler's scratch lives in the second weight slot, which is not
     // written before the prologue's barrier
     int* sched = reinterpret_cast<int*>(smem + (TRI_B ? A_BYTES : B_REGION + B_BYTES));  // second early slot
@@ -224,11 +216,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
 
     int l0 = 0, l1 = L_BYTES, l2 = 2 * L_BYTES;  // late-operand slots of tiles kt, kt+1, kt+2
     int e0 = 0, e1 = E_BYTES;                    // early-operand slots of tiles kt, kt+1
-#ifdef MOE_PIPE_TIMING
-    unsigned long long tk_wait = 0, tk_bar = 0;
-    const unsigned long long tk_begin = __builtin_amdgcn_s_memtime();
-    const unsigned long long rt_begin = __builtin_amdgcn_s_memrealtime();
-#endif
     for (int kt = 0; kt < KT; ++kt) {
         const uint8_t* ca = a_ptr(e0, l0);
         const uint8_t* cb = b_ptr(e0, l0);
@@ -242,18 +229,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
         // early(kt+1) was issued before late(kt+2) in this period and late(kt+1) a
         // period ago: all but the PL youngest loads must have landed; this wave's
         // reads of tile kt are in registers (lgkmcnt(0))
-#ifdef MOE_PIPE_TIMING
-        const unsigned long long tk0 = __builtin_amdgcn_s_memtime();
-        __builtin_amdgcn_s_waitcnt((PL & 0xF) | ((PL >> 4) << 14));
-        const unsigned long long tk1 = __builtin_amdgcn_s_memtime();
-        __builtin_amdgcn_s_barrier();
-        const unsigned long long tk2 = __builtin_amdgcn_s_memtime();
-        tk_wait += tk1 - tk0;
-        tk_bar += tk2 - tk1;
-#else
         __builtin_amdgcn_s_waitcnt((PL & 0xF) | ((PL >> 4) << 14));
         __builtin_amdgcn_s_barrier();
-#endif
         __builtin_amdgcn_sched_barrier(0);
         // k-step 3: first fragments of tile kt+1; tile kt's early slot is free,
         // the head of early(kt+2) goes into it
@@ -266,35 +243,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
         e0 = e1;
         e1 = te;
     }
-#ifdef MOE_PIPE_TIMING
-    const unsigned long long tk_end = __builtin_amdgcn_s_memtime();
-    const unsigned long long rt_end = __builtin_amdgcn_s_memrealtime();
-#endif
     wait_vmcnt0();  // loads past the end of K may still be landing in LDS
     store_tile<FM, FN, WM, WN, BN, SWIGLU>(acc, tile, C, N, n0, wm, wn, lane);
-#ifdef MOE_PIPE_TIMING
-    wait_vmcnt0();
-    if (lane == 0 && blockIdx.x < 8192) {
-        unsigned long long* o = g_pipe3_ticks + ((size_t)blockIdx.x * 8 + wave) * 8;
-        o[0] = tk_end - tk_begin;
-        o[1] = tk_wait;
-        o[2] = tk_bar;
-        o[3] = tk_begin;
-        o[4] = tk_entry;
-        o[5] = __builtin_amdgcn_s_memtime();
-        o[6] = rt_begin;
-        o[7] = rt_end;
-    }
-#endif
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU, int DIST, bool TRI_B>
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
 void launch_pipe3(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B0,
                   const void* B1, void* C, hipStream_t s) {
     constexpr int OUTN = SWIGLU ? BN / 2 : BN;
-    constexpr size_t smem = (size_t)(TRI_B ? 2 * BM + 3 * BN : 3 * BM + 2 * BN) * 64 * 2;
+    constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
     const int ntn = (N + OUTN - 1) / OUTN;
-    auto kern = gemm_bf16_pipe3_kernel<BM, BN, WGM, WGN, SWIGLU, DIST, TRI_B>;
+    auto kern = gemm_bf16_pipe3_kernel<BM, BN, WGM, WGN, SWIGLU>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -307,12 +266,12 @@ void launch_pipe3(const void* A, const int32_t* offsets, int r_max, int E, int N
                        static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C), ntn);
 }
 
-template <int BM, int BN, int WGM, int WGN, int DIST, bool TRI_B = false>
+template <int BM, int BN, int WGM, int WGN>
 void run_pipe3_pair(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                     const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm,
                     int phase, hipStream_t s) {
-    if (phase & 1) launch_pipe3<BM, BN, WGM, WGN, true, DIST, TRI_B>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, s);
-    if (phase & 2) launch_pipe3<BM, BN, WGM, WGN, false, DIST, TRI_B>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
+    if (phase & 1) launch_pipe3<BM, BN, WGM, WGN, true>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, s);
+    if (phase & 2) launch_pipe3<BM, BN, WGM, WGN, false>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
 }
 
 }  // namespace
@@ -321,12 +280,8 @@ bool launch_pipe3_ffn(const void* x_perm, const int32_t* offsets, int r_max, int
                       const void* w_gate, const void* w_up, const void* w_down, void* h,
                       void* y_perm, int variant, int phase, hipStream_t s) {
     switch (variant) {
-        case 30: run_pipe3_pair<256, 256, 2, 2, 0>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
-        case 31: run_pipe3_pair<256, 256, 2, 4, 0>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
-        case 32: run_pipe3_pair<256, 256, 2, 2, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
-        case 33: run_pipe3_pair<256, 256, 2, 4, 1>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
-        case 34: run_pipe3_pair<256, 256, 2, 2, 0, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
-        case 35: run_pipe3_pair<256, 256, 2, 4, 0, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 30: run_pipe3_pair<256, 256, 2, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 31: run_pipe3_pair<256, 256, 2, 4>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         default: return false;
     }
 }

@@ -164,12 +164,8 @@ inline int grid_for(int r_max, int E, int BM, int ntn) {
 }
 
 
-// pipelined MFMA kernels (gemm_pipe.hip); returns false for an unknown variant
-bool launch_pipe_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
-                     const void* w_gate, const void* w_up, const void* w_down, void* h,
-                     void* y_perm, int variant, int phase, hipStream_t s);
-
-// pipelined MFMA kernels with three activation stages (gemm_pipe3.hip)
+// pipelined MFMA kernels with three activation stages (gemm_pipe3.hip); returns
+// false for an unknown variant
 bool launch_pipe3_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                       const void* w_gate, const void* w_up, const void* w_down, void* h,
                       void* y_perm, int variant, int phase, hipStream_t s);

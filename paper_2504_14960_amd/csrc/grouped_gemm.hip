@@ -367,19 +367,13 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
         return true;
     if (variant >= 30 && launch_pipe3_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, variant, phase, s))
         return true;
-    if (variant >= 10 && launch_pipe_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, variant, phase, s))
-        return true;
+    // baseline kernel: two LDS stages, one workgroup per tile
     switch (variant) {
         default:
         case 1: run_pair<256, 256, 64, 2, 2, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
         case 2: run_pair<256, 256, 64, 2, 2, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
-        case 3: run_pair<256, 256, 64, 2, 4, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
-        case 4: run_pair<256, 256, 64, 2, 4, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
         case 5: run_pair<128, 256, 64, 2, 2, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
-        case 6: run_pair<128, 256, 64, 2, 2, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
         case 7: run_pair<128, 128, 64, 2, 2, false>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
-        case 9: run_pair<256, 256, 32, 2, 2, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
-        case 8: run_pair<128, 128, 64, 2, 2, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); break;
     }
     return true;
 }
