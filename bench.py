@@ -180,8 +180,9 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    stage_ms = {nm: sum(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(args.steps)) / args.steps
+    per_step = {nm: sorted(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(args.steps))
                 for j, nm in enumerate(stage_names)}
+    stage_ms = {nm: sum(v) / len(v) for nm, v in per_step.items()}
 
     # algorithmic work (useful bytes / flops only)
     maps = 8 * T * K
@@ -200,7 +201,19 @@ def main():
         ms = stage_ms[nm]
         rate = work / (ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
         peak = PEAK_BF16_TFLOPS if unit == "TFLOP/s" else PEAK_HBM_GBS
-        stages[nm] = {"ms": round(ms, 4), "achieved": round(rate, 1), "unit": unit, "frac": round(rate / peak, 4)}
+        v = per_step[nm]
+        stages[nm] = {"ms": round(ms, 4), "ms_median": round(v[len(v) // 2], 4), "ms_min": round(v[0], 4),
+                      "achieved": round(rate, 1), "unit": unit, "frac": round(rate / peak, 4)}
+    # what the two rooflines allow for the ragged expert GEMMs: per expert the larger of its MFMA time and the
+    # time to stream its weights and rows once from HBM, summed over the experts (they share the chip in turn)
+    def attainable_ms(flop_per_row, w_bytes, row_bytes):
+        t = 0.0
+        for n in counts:
+            if n > 0:
+                t += max(flop_per_row * n / (PEAK_BF16_TFLOPS * 1e12), (w_bytes + n * row_bytes) / (PEAK_HBM_GBS * 1e9))
+        return round(t * 1e3, 4)
+    stages["gate_up"]["attainable_ms"] = attainable_ms(4.0 * H * F, 2 * H * F * es, (H + F) * es)
+    stages["down"]["attainable_ms"] = attainable_ms(2.0 * H * F, H * F * es, (H + F) * es)
 
     dom = stages["gate_up"]
     roofline = {"kernel": "gate/up grouped GEMM (moe_expert_gate_up)", "bound": "mfma", "achieved": dom["achieved"],

@@ -1,4 +1,4 @@
-"""ctypes access to the CPU oracle (oracle/moe_oracle.c).
+"""ctypes access to the CPU oracle (oracle/moe_oracle.c, oracle/moe_oracle_fp8.c).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke()``
 and by ``bench.py``'s cpu_baseline leg, never by the product package.
@@ -27,6 +27,16 @@ def lib() -> C.CDLL:
         L.oracle_capacity.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int]
         L.oracle_permute.restype = C.c_int
         L.oracle_layer_forward.restype = C.c_int
+        L.oracle_fp8_decode.restype = C.c_double
+        L.oracle_fp8_decode.argtypes = [C.c_uint8]
+        L.oracle_fp8_encode.restype = C.c_uint8
+        L.oracle_fp8_encode.argtypes = [C.c_float]
+        L.oracle_fp8_delayed_scale.restype = C.c_float
+        L.oracle_fp8_delayed_scale.argtypes = [C.c_void_p, C.c_int, C.c_int]
+        L.oracle_fp8_quantize.argtypes = [C.c_void_p, C.c_int, C.c_size_t, C.c_float, C.c_void_p, C.c_void_p]
+        L.oracle_experts_fp8.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_double, C.c_double, C.c_float, C.c_double, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -203,3 +213,60 @@ def dense_bruteforce(x, w_router, bias, w_gate, w_up, w_down, K: int, renormaliz
                                   T, H, E, K, F, int(bool(renormalize)), int(capacity_rows), _dt(x),
                                   _p(g), _p(y))
     return y, g
+
+
+# ---------------------------------------------------------------- FP8 (E4M3) variant
+def fp8_decode(codes: np.ndarray) -> np.ndarray:
+    """Values (float64) of E4M3 codes (uint8), element by element."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    f = lib().oracle_fp8_decode
+    return np.array([f(int(c)) for c in codes.ravel()], dtype=np.float64).reshape(codes.shape)
+
+
+def fp8_encode(values: np.ndarray) -> np.ndarray:
+    """Nearest E4M3 codes (ties to even, saturating) of float32 values, element by element."""
+    values = np.ascontiguousarray(values, dtype=np.float32)
+    f = lib().oracle_fp8_encode
+    return np.array([f(float(v)) for v in values.ravel()], dtype=np.uint8).reshape(values.shape)
+
+
+def fp8_quantize(src: np.ndarray, scale: float, amax_in: float = 0.0) -> Tuple[np.ndarray, float]:
+    """codes = encode(fp32(src * scale)); returns (codes, max(amax_in, max |src|))."""
+    src = np.ascontiguousarray(src)
+    dst = np.empty(src.shape, dtype=np.uint8)
+    amax = np.array([amax_in], dtype=np.float32)
+    lib().oracle_fp8_quantize(_p(src), _dt(src), src.size, float(scale), _p(dst), _p(amax))
+    return dst, float(amax[0])
+
+
+def fp8_delayed_scale(amax_history, margin: int = 0) -> float:
+    h = np.ascontiguousarray(amax_history, dtype=np.float32)
+    return float(lib().oracle_fp8_delayed_scale(_p(h), int(h.size), int(margin)))
+
+
+class Fp8Experts:
+    def __init__(self, hq, h_val, amax_h, y):
+        self.hq = hq          # [R, F] uint8 E4M3 codes of h * scale_h
+        self.h_val = h_val    # [R, F] float64, h before quantisation (or None)
+        self.amax_h = amax_h  # max |h|
+        self.y = y            # [R, H] float64
+
+
+def experts_fp8(xq: np.ndarray, offsets: np.ndarray, wg: np.ndarray, wu: np.ndarray, wd: np.ndarray,
+                dq_gate: float, dq_up: float, scale_h: float, dq_down: float,
+                want_h: bool = False) -> Fp8Experts:
+    E, F, H = wg.shape
+    assert wu.shape == (E, F, H) and wd.shape == (E, H, F)
+    for a in (xq, wg, wu, wd):
+        assert a.dtype == np.uint8
+    offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+    R = int(offsets[E])
+    assert xq.shape[0] >= R and xq.shape[1] == H
+    hq = np.zeros((R, F), dtype=np.uint8)
+    h_val = np.zeros((R, F), dtype=np.float64) if want_h else None
+    y = np.zeros((R, H), dtype=np.float64)
+    amax = np.zeros(1, dtype=np.float64)
+    lib().oracle_experts_fp8(_p(np.ascontiguousarray(xq)), _p(offsets), E, H, F, _p(np.ascontiguousarray(wg)),
+                             _p(np.ascontiguousarray(wu)), _p(np.ascontiguousarray(wd)), float(dq_gate),
+                             float(dq_up), float(scale_h), float(dq_down), _p(hq), _p(h_val), _p(amax), _p(y))
+    return Fp8Experts(hq, h_val, float(amax[0]), y)
