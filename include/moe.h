@@ -200,6 +200,60 @@ moe_status_t moe_layer_forward(const void* x, const void* w_router, const float*
                                int capacity, moe_dtype_t dt, void* y, void* workspace,
                                size_t workspace_bytes, moe_stream_t stream);
 
+/*
+ * FP8 variant of a3 with per-tensor delayed scaling (Section 4.5, "FP8 Training
+ * Performance"; the paper names the recipe, the definitions here are this
+ * library's reading of it).
+ *
+ * FP8 is the OCP E4M3 format (bias 7, largest finite value 448, no infinities).
+ * A tensor t is held as codes q = e4m3(t * scale): round to nearest, ties to
+ * even, magnitudes above 448 saturate, NaN stays NaN; the product is formed in
+ * fp32.  "Delayed" scaling: the scale of a step is computed from the largest
+ * |t| of EARLIER steps (moe_fp8_delayed_scale over a history of amax values the
+ * caller keeps); the current step only records its own amax.
+ */
+
+/* Host only: 448 / (max(amax_history[0..len)) * 2^margin); non-finite entries
+ * are ignored; 1.0 if nothing positive has been recorded yet. */
+float moe_fp8_delayed_scale(const float* amax_history, int len, int margin);
+
+/* dst[i] = e4m3(src[i] * scale) for i < n; src is dt (fp32 or bf16), dst n
+ * bytes.  If amax is non-NULL, *amax (device, fp32) becomes max(*amax, max_i
+ * |src[i]|): the caller zeroes it when a new step starts.  src and dst 16-byte
+ * aligned. */
+moe_status_t moe_fp8_quantize(const void* src, moe_dtype_t dt, size_t n, float scale, void* dst,
+                              float* amax, moe_stream_t stream);
+
+/*
+ * Grouped SwiGLU expert FFN on E4M3 operands.  x_perm [R_max,H], w_gate, w_up
+ * [E,F,H], w_down [E,H,F] are E4M3 codes quantised with scales s_x, s_gate,
+ * s_up, s_down.  For every expert over its rows:
+ *
+ *   g = dq_gate * (x_perm . w_gate^T)      dq_gate = 1 / (s_x * s_gate)
+ *   u = dq_up   * (x_perm . w_up^T)        dq_up   = 1 / (s_x * s_up)
+ *   h = silu(g) * u;  *amax_h = max(*amax_h, max |h|)   (amax_h may be NULL)
+ *   h_fp8 = e4m3(h * scale_h)              [R_max,F] E4M3, workspace and output
+ *   y_perm = dq_down * (h_fp8 . w_down^T)  dq_down = 1 / (scale_h * s_down), bf16
+ *
+ * with fp32 accumulation.  scale_h is this step's (delayed) scale of h.  H and
+ * F must be multiples of 128 and at least 256, E <= 256; other shapes return
+ * MOE_ERR_UNSUPPORTED.  Rows in [R, R_max) are not touched.
+ */
+moe_status_t moe_grouped_gemm_swiglu_fp8(const void* x_perm_fp8, const int32_t* expert_offsets,
+                                         int R_max, int H, int F, int E, const void* w_gate_fp8,
+                                         const void* w_up_fp8, const void* w_down_fp8, float dq_gate,
+                                         float dq_up, float scale_h, float dq_down, void* h_fp8,
+                                         float* amax_h, void* y_perm_bf16, moe_stream_t stream);
+
+/* The two halves of moe_grouped_gemm_swiglu_fp8, for per-stage timing. */
+moe_status_t moe_expert_gate_up_fp8(const void* x_perm_fp8, const int32_t* expert_offsets, int R_max,
+                                    int H, int F, int E, const void* w_gate_fp8, const void* w_up_fp8,
+                                    float dq_gate, float dq_up, float scale_h, void* h_fp8,
+                                    float* amax_h, moe_stream_t stream);
+moe_status_t moe_expert_down_fp8(const void* h_fp8, const int32_t* expert_offsets, int R_max, int H,
+                                 int F, int E, const void* w_down_fp8, float dq_down,
+                                 void* y_perm_bf16, moe_stream_t stream);
+
 /* Tuning knobs for experiments (process-wide, not thread-safe; defaults are
  * the tuned ones).  Unknown names return MOE_ERR_INVALID_ARG.  Names:
  * "gemm_variant" (0 = auto); "gemm_workgroups" (workgroups launched by the

@@ -10,8 +10,13 @@ from .binding import (  # noqa: F401
     MoeError,
     capacity_from_factor,
     expert_down,
+    expert_down_fp8,
     expert_gate_up,
+    expert_gate_up_fp8,
+    fp8_delayed_scale,
+    fp8_quantize,
     grouped_gemm_swiglu,
+    grouped_gemm_swiglu_fp8,
     layer_forward,
     layer_workspace_bytes,
     layer_workspace_layout,

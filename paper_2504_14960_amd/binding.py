@@ -72,6 +72,17 @@ def lib() -> C.CDLL:
     L.moe_layer_forward.argtypes = [vp] * 9 + [i] * 9 + [vp, vp, sz, vp]
     L.moe_set_option.restype = i
     L.moe_set_option.argtypes = [C.c_char_p, i]
+    f = C.c_float
+    L.moe_fp8_delayed_scale.restype = f
+    L.moe_fp8_delayed_scale.argtypes = [C.POINTER(f), i, i]
+    L.moe_fp8_quantize.restype = i
+    L.moe_fp8_quantize.argtypes = [vp, i, sz, f, vp, vp, vp]
+    L.moe_grouped_gemm_swiglu_fp8.restype = i
+    L.moe_grouped_gemm_swiglu_fp8.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, f, f, f, f, vp, vp, vp, vp]
+    L.moe_expert_gate_up_fp8.restype = i
+    L.moe_expert_gate_up_fp8.argtypes = [vp, vp, i, i, i, i, vp, vp, f, f, f, vp, vp, vp]
+    L.moe_expert_down_fp8.restype = i
+    L.moe_expert_down_fp8.argtypes = [vp, vp, i, i, i, i, vp, f, vp, vp]
     _lib = L
     return L
 
@@ -180,6 +191,48 @@ def unpermute_combine(y_perm: torch.Tensor, row_of_assign: torch.Tensor, topk_ga
     R_max, H = y_perm.shape
     _check(lib().moe_unpermute_combine(_ptr(y_perm), _ptr(row_of_assign), _ptr(topk_gate), _ptr(addend),
                                        T, H, K, R_max, _dt(y), _ptr(y), _stream()))
+
+
+# ---- FP8 (E4M3) variant of the expert FFN; E4M3 tensors are torch.uint8 (codes) ----
+def fp8_delayed_scale(amax_history, margin: int = 0) -> float:
+    h = [float(v) for v in amax_history]
+    arr = (C.c_float * max(len(h), 1))(*h)
+    return float(lib().moe_fp8_delayed_scale(arr, len(h), int(margin)))
+
+
+def fp8_quantize(src: torch.Tensor, scale: float, dst: torch.Tensor, amax: Optional[torch.Tensor] = None) -> None:
+    if dst.dtype != torch.uint8 or dst.numel() != src.numel():
+        raise ValueError("dst must be a uint8 tensor with as many elements as src")
+    _check(lib().moe_fp8_quantize(_ptr(src), _dt(src), src.numel(), float(scale), _ptr(dst), _ptr(amax), _stream()))
+
+
+def grouped_gemm_swiglu_fp8(x_perm: torch.Tensor, expert_offsets: torch.Tensor, w_gate: torch.Tensor,
+                            w_up: torch.Tensor, w_down: torch.Tensor, dq_gate: float, dq_up: float,
+                            scale_h: float, dq_down: float, h: torch.Tensor, amax_h: Optional[torch.Tensor],
+                            y_perm: torch.Tensor) -> None:
+    R_max, H = x_perm.shape
+    E, F, _ = w_gate.shape
+    _check(lib().moe_grouped_gemm_swiglu_fp8(_ptr(x_perm), _ptr(expert_offsets), R_max, H, F, E, _ptr(w_gate),
+                                             _ptr(w_up), _ptr(w_down), float(dq_gate), float(dq_up), float(scale_h),
+                                             float(dq_down), _ptr(h), _ptr(amax_h), _ptr(y_perm), _stream()))
+
+
+def expert_gate_up_fp8(x_perm: torch.Tensor, expert_offsets: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor,
+                       dq_gate: float, dq_up: float, scale_h: float, h: torch.Tensor,
+                       amax_h: Optional[torch.Tensor]) -> None:
+    R_max, H = x_perm.shape
+    E, F, _ = w_gate.shape
+    _check(lib().moe_expert_gate_up_fp8(_ptr(x_perm), _ptr(expert_offsets), R_max, H, F, E, _ptr(w_gate), _ptr(w_up),
+                                        float(dq_gate), float(dq_up), float(scale_h), _ptr(h), _ptr(amax_h),
+                                        _stream()))
+
+
+def expert_down_fp8(h: torch.Tensor, expert_offsets: torch.Tensor, w_down: torch.Tensor, dq_down: float,
+                    y_perm: torch.Tensor) -> None:
+    R_max, F = h.shape
+    E, H, _ = w_down.shape
+    _check(lib().moe_expert_down_fp8(_ptr(h), _ptr(expert_offsets), R_max, H, F, E, _ptr(w_down), float(dq_down),
+                                     _ptr(y_perm), _stream()))
 
 
 def layer_workspace_bytes(T: int, H: int, E: int, K: int, F: int, Fs: int, capacity: int, dtype: int) -> int:

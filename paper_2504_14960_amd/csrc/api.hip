@@ -300,6 +300,82 @@ moe_status_t moe_layer_forward(const void* x, const void* w_router, const float*
     return moe_unpermute_combine(ws + L.y_perm, roa, gate, addend, T, H, K, L.r_max, dt, y, stream);
 }
 
+float moe_fp8_delayed_scale(const float* amax_history, int len, int margin) {
+    float m = 0.f;
+    for (int i = 0; amax_history && i < len; ++i)
+        if (std::isfinite(amax_history[i]) && amax_history[i] > m) m = amax_history[i];
+    if (!(m > 0.f)) return 1.f;
+    return (float)(448.0 / ((double)m * std::ldexp(1.0, margin)));
+}
+
+moe_status_t moe_fp8_quantize(const void* src, moe_dtype_t dt, size_t n, float scale, void* dst,
+                              float* amax, moe_stream_t stream) {
+    static const char* fn = "moe_fp8_quantize";
+    if (dt != MOE_F32 && dt != MOE_BF16) return fail(MOE_ERR_INVALID_ARG, "%s: unknown dtype %d", fn, (int)dt);
+    if (!std::isfinite(scale) || !(scale > 0.f)) return fail(MOE_ERR_INVALID_ARG, "%s: scale must be positive and finite", fn);
+    if (n == 0) return MOE_OK;
+    REQUIRE_PTR(fn, src);
+    REQUIRE_PTR(fn, dst);
+    if (amax && (reinterpret_cast<uintptr_t>(amax) & 3u)) return fail(MOE_ERR_INVALID_ARG, "%s: amax is not 4-byte aligned", fn);
+    launch_fp8_quantize(src, dt, n, scale, dst, amax, static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
+static moe_status_t expert_ffn_fp8(const char* fn, int phase, const void* x_perm, const int32_t* expert_offsets,
+                                   int R_max, int H, int F, int E, const void* w_gate, const void* w_up,
+                                   const void* w_down, float dq_gate, float dq_up, float scale_h, float dq_down,
+                                   void* h, float* amax_h, void* y_perm, moe_stream_t stream) {
+    if (R_max < 0 || H <= 0 || F <= 0 || E <= 0)
+        return fail(MOE_ERR_INVALID_ARG, "%s: need R_max >= 0 and H, F, E > 0", fn);
+    if (E > kMaxExperts) return fail(MOE_ERR_UNSUPPORTED, "%s: E=%d exceeds the limit %d", fn, E, kMaxExperts);
+    if (!fp8_ffn_supported(H, F))
+        return fail(MOE_ERR_UNSUPPORTED, "%s: H=%d and F=%d must be multiples of 128 and at least 256", fn, H, F);
+    if ((phase & 1) && !(std::isfinite(dq_gate) && std::isfinite(dq_up) && std::isfinite(scale_h) && scale_h > 0.f))
+        return fail(MOE_ERR_INVALID_ARG, "%s: dq_gate, dq_up and scale_h must be finite, scale_h positive", fn);
+    if ((phase & 2) && !std::isfinite(dq_down)) return fail(MOE_ERR_INVALID_ARG, "%s: dq_down must be finite", fn);
+    if (R_max == 0) return MOE_OK;
+    REQUIRE_PTR(fn, expert_offsets);
+    REQUIRE_PTR(fn, h);
+    if (phase & 1) {
+        REQUIRE_PTR(fn, x_perm);
+        REQUIRE_PTR(fn, w_gate);
+        REQUIRE_PTR(fn, w_up);
+        if (amax_h && (reinterpret_cast<uintptr_t>(amax_h) & 3u))
+            return fail(MOE_ERR_INVALID_ARG, "%s: amax_h is not 4-byte aligned", fn);
+    }
+    if (phase & 2) {
+        REQUIRE_PTR(fn, w_down);
+        REQUIRE_PTR(fn, y_perm);
+    }
+    launch_expert_ffn_fp8(x_perm, expert_offsets, R_max, H, F, E, w_gate, w_up, w_down, dq_gate, dq_up, scale_h,
+                          dq_down, h, amax_h, y_perm, phase, static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
+moe_status_t moe_grouped_gemm_swiglu_fp8(const void* x_perm_fp8, const int32_t* expert_offsets,
+                                         int R_max, int H, int F, int E, const void* w_gate_fp8,
+                                         const void* w_up_fp8, const void* w_down_fp8, float dq_gate,
+                                         float dq_up, float scale_h, float dq_down, void* h_fp8,
+                                         float* amax_h, void* y_perm_bf16, moe_stream_t stream) {
+    return expert_ffn_fp8("moe_grouped_gemm_swiglu_fp8", 3, x_perm_fp8, expert_offsets, R_max, H, F, E, w_gate_fp8,
+                          w_up_fp8, w_down_fp8, dq_gate, dq_up, scale_h, dq_down, h_fp8, amax_h, y_perm_bf16, stream);
+}
+
+moe_status_t moe_expert_gate_up_fp8(const void* x_perm_fp8, const int32_t* expert_offsets, int R_max,
+                                    int H, int F, int E, const void* w_gate_fp8, const void* w_up_fp8,
+                                    float dq_gate, float dq_up, float scale_h, void* h_fp8,
+                                    float* amax_h, moe_stream_t stream) {
+    return expert_ffn_fp8("moe_expert_gate_up_fp8", 1, x_perm_fp8, expert_offsets, R_max, H, F, E, w_gate_fp8,
+                          w_up_fp8, nullptr, dq_gate, dq_up, scale_h, 0.f, h_fp8, amax_h, nullptr, stream);
+}
+
+moe_status_t moe_expert_down_fp8(const void* h_fp8, const int32_t* expert_offsets, int R_max, int H,
+                                 int F, int E, const void* w_down_fp8, float dq_down,
+                                 void* y_perm_bf16, moe_stream_t stream) {
+    return expert_ffn_fp8("moe_expert_down_fp8", 2, nullptr, expert_offsets, R_max, H, F, E, nullptr, nullptr,
+                          w_down_fp8, 0.f, 0.f, 1.f, dq_down, const_cast<void*>(h_fp8), nullptr, y_perm_bf16, stream);
+}
+
 moe_status_t moe_set_option(const char* name, int value) {
     if (name && strcmp(name, "gemm_workgroups") == 0) {
         if (value < 0) return fail(MOE_ERR_INVALID_ARG, "moe_set_option: gemm_workgroups must be >= 0");

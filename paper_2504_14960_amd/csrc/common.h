@@ -64,4 +64,14 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
 
 void launch_fill_i32(int32_t* p, int n, int32_t v0, int32_t step, hipStream_t s);
 
+// FP8 (E4M3) path of the expert FFN: per-tensor quantisation with amax, and the
+// two grouped GEMMs on quantised operands (phase bits as above)
+void launch_fp8_quantize(const void* src, moe_dtype_t dt, size_t n, float scale, void* dst, float* amax,
+                         hipStream_t s);
+bool fp8_ffn_supported(int H, int F);
+void launch_expert_ffn_fp8(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                           const void* w_gate, const void* w_up, const void* w_down, float dq_gate, float dq_up,
+                           float scale_h, float dq_down, void* h, float* amax_h, void* y_perm, int phase,
+                           hipStream_t s);
+
 }  // namespace moe
