@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 NSETS = 4                   # rotating activation/workspace sets (defeats the 256 MB Infinity Cache)
 
@@ -39,6 +40,10 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="mixtral8x22b")
+    ap.add_argument("--precision", default="bf16", choices=["bf16", "fp8"],
+                    help="fp8: expert FFN on E4M3 operands with delayed per-tensor scaling (weights quantised "
+                         "beforehand and resident, activations quantised inside the timed step); a separate "
+                         "experiment, the headline metric is the bf16 run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -138,6 +143,32 @@ def main():
             s["s_y"] = torch.empty((T, H), dtype=tdt, device="cuda")
         sets.append(s)
 
+    fp8 = args.precision == "fp8"
+    if fp8:
+        if not bf16 or Fs:
+            print("bench.py: --precision fp8 needs a bf16 workload without a shared expert", file=sys.stderr)
+            sys.exit(2)
+        # delayed scaling: the scales come from amax values of an earlier step; here one calibration pass
+        # (outside the timed region) plays that earlier step
+        def amax_of(t):
+            a = torch.zeros(1, dtype=torch.float32, device="cuda")
+            moe.fp8_quantize(t, 1.0, torch.empty(t.numel(), dtype=torch.uint8, device="cuda"), a)
+            return float(a.item())
+        f8 = {"s": {}, "w": {}}
+        for k in ("w_gate", "w_up", "w_down"):
+            f8["s"][k] = moe.fp8_delayed_scale([amax_of(w[k])])
+            f8["w"][k] = torch.empty(w[k].shape, dtype=torch.uint8, device="cuda")
+            moe.fp8_quantize(w[k], f8["s"][k], f8["w"][k])
+        f8["s"]["x"] = moe.fp8_delayed_scale([amax_of(sets[0]["x"])])
+        f8["dq_gate"] = 1.0 / (f8["s"]["x"] * f8["s"]["w_gate"])
+        f8["dq_up"] = 1.0 / (f8["s"]["x"] * f8["s"]["w_up"])
+        f8["scale_h"] = 1.0
+        for s in sets:
+            s["xq"] = torch.empty((r_max, H), dtype=torch.uint8, device="cuda")
+            s["hq"] = torch.empty((r_max, F), dtype=torch.uint8, device="cuda")
+            s["amax"] = torch.zeros(2, dtype=torch.float32, device="cuda")
+        del w["w_gate"], w["w_up"], w["w_down"]
+
     stage_names = ["router", "permute", "gate_up", "down"] + (["shared"] if Fs else []) + ["combine"]
 
     def step(s, events=None):
@@ -147,13 +178,28 @@ def main():
         mark(0)
         moe.router_topk(s["x"], w["w_router"], bias, s["logits"], K, cfg.renormalize, s["idx"], s["gate"])
         mark(1)
-        moe.permute(s["x"], s["idx"], E, capacity, s["x_perm"], s["counts"], s["offsets"], s["roa"], s["aor"], s["pws"])
-        mark(2)
-        moe.expert_gate_up(s["x_perm"], s["offsets"], w["w_gate"], w["w_up"], s["h"])
-        mark(3)
-        moe.expert_down(s["h"], s["offsets"], w["w_down"], s["y_perm"])
-        mark(4)
-        n = 4
+        if fp8:
+            # the amax cells of this step (x, h) start from zero; the permute writes x_perm as E4M3 directly
+            s["amax"].zero_()
+            moe.permute_fp8(s["x"], s["idx"], E, capacity, f8["s"]["x"], s["xq"], s["counts"], s["offsets"],
+                            s["roa"], s["aor"], s["amax"][0:1], s["pws"])
+            mark(2)
+            moe.expert_gate_up_fp8(s["xq"], s["offsets"], f8["w"]["w_gate"], f8["w"]["w_up"], f8["dq_gate"],
+                                   f8["dq_up"], f8["scale_h"], s["hq"], s["amax"][1:2])
+            mark(3)
+            moe.expert_down_fp8(s["hq"], s["offsets"], f8["w"]["w_down"],
+                                1.0 / (f8["scale_h"] * f8["s"]["w_down"]), s["y_perm"])
+            mark(4)
+            n = 4
+        else:
+            moe.permute(s["x"], s["idx"], E, capacity, s["x_perm"], s["counts"], s["offsets"], s["roa"], s["aor"],
+                        s["pws"])
+            mark(2)
+            moe.expert_gate_up(s["x_perm"], s["offsets"], w["w_gate"], w["w_up"], s["h"])
+            mark(3)
+            moe.expert_down(s["h"], s["offsets"], w["w_down"], s["y_perm"])
+            mark(4)
+            n = 4
         addend = None
         if Fs:
             moe.grouped_gemm_swiglu(s["x"], s["s_off"], w["ws_gate"].unsqueeze(0), w["ws_up"].unsqueeze(0),
@@ -164,6 +210,11 @@ def main():
         moe.unpermute_combine(s["y_perm"], s["roa"], s["gate"], addend, s["y"])
         mark(n + 1)
 
+    if fp8:
+        # calibration step: records max |h| with a neutral scale, as the previous step of a delayed-scaling run would
+        step(sets[0])
+        torch.cuda.synchronize()
+        f8["scale_h"] = moe.fp8_delayed_scale([float(sets[0]["amax"][1].item())])
     for i in range(args.warmup):
         step(sets[i % NSETS])
     torch.cuda.synchronize()
@@ -195,12 +246,14 @@ def main():
     }
     if Fs:
         alg["shared"] = ("TFLOP/s", 6.0 * T * H * Fs)
+    if fp8:
+        alg["permute"] = ("GB/s", T * H * es + R * H + maps)   # bf16 rows in, E4M3 rows out
     stages = {}
     for nm in stage_names:
         unit, work = alg[nm]
         ms = stage_ms[nm]
         rate = work / (ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9)
-        peak = PEAK_BF16_TFLOPS if unit == "TFLOP/s" else PEAK_HBM_GBS
+        peak = (PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS) if unit == "TFLOP/s" else PEAK_HBM_GBS
         v = per_step[nm]
         stages[nm] = {"ms": round(ms, 4), "ms_median": round(v[len(v) // 2], 4), "ms_min": round(v[0], 4),
                       "achieved": round(rate, 1), "unit": unit, "frac": round(rate / peak, 4)}
@@ -210,15 +263,17 @@ def main():
         t = 0.0
         for n in counts:
             if n > 0:
-                t += max(flop_per_row * n / (PEAK_BF16_TFLOPS * 1e12), (w_bytes + n * row_bytes) / (PEAK_HBM_GBS * 1e9))
+                t += max(flop_per_row * n / ((PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS) * 1e12),
+                         (w_bytes + n * row_bytes) / (PEAK_HBM_GBS * 1e9))
         return round(t * 1e3, 4)
-    stages["gate_up"]["attainable_ms"] = attainable_ms(4.0 * H * F, 2 * H * F * es, (H + F) * es)
-    stages["down"]["attainable_ms"] = attainable_ms(2.0 * H * F, H * F * es, (H + F) * es)
+    ges = 1 if fp8 else es   # bytes per GEMM operand element
+    stages["gate_up"]["attainable_ms"] = attainable_ms(4.0 * H * F, 2 * H * F * ges, (H + F) * ges)
+    stages["down"]["attainable_ms"] = attainable_ms(2.0 * H * F, H * F * ges, H * es + F * ges)
 
     dom = stages["gate_up"]
     roofline = {"kernel": "gate/up grouped GEMM (moe_expert_gate_up)", "bound": "mfma", "achieved": dom["achieved"],
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom["frac"],
-                "traffic": MEASURED_TRAFFIC.get(cfg.name)}
+                "peak": PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom["frac"],
+                "traffic": None if fp8 else MEASURED_TRAFFIC.get(cfg.name)}
 
     out = {
         "metric": "MoE layer fwd tokens/s; grouped-GEMM % bf16 MFMA peak; permute GB/s % HBM",
@@ -231,12 +286,13 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": cfg.dtype,
+        "dtype": "fp8e4m3" if fp8 else cfg.dtype,
         "data": "synthetic",
         "config": {"workload": f"{cfg.name} layer: T={T} H={H} E={E} K={K} F={F}"
                                + (f" shared_F={Fs}" if Fs else "")
                                + (f" capacity={capacity}" if capacity else " dropless")
-                               + (f" bias={cfg.bias}" if cfg.bias else ""),
+                               + (f" bias={cfg.bias}" if cfg.bias else "")
+                               + (" [expert FFN in FP8 E4M3, delayed scaling, weights pre-quantised]" if fp8 else ""),
                    "kept_rows": R, "rows_per_expert_min_max": [min(counts), max(counts)],
                    "buffer_sets": NSETS, "input_generation_s": round(t_gen, 1)},
         "roofline": roofline,
@@ -244,7 +300,7 @@ def main():
         "context": "the paper reports 49.3 % (Mixtral 8x22B) and 39.0 % (Qwen2-57B-A14B) MFU for whole training "
                    "steps on H100 clusters: other hardware, other scope, shown for orientation only",
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not fp8:
         out["cpu_baseline"] = cpu_baseline(inp, capacity, args.cpu_seconds)
     print(json.dumps(out))
 

@@ -225,6 +225,20 @@ moe_status_t moe_fp8_quantize(const void* src, moe_dtype_t dt, size_t n, float s
                               float* amax, moe_stream_t stream);
 
 /*
+ * a2 fused with the quantisation of its output: as moe_permute on a bf16 x, but
+ * x_perm is written as E4M3 codes, x_perm_fp8[row,:] = e4m3(x[token,:] * scale)
+ * ([R_max,H] bytes), and *amax (device, may be NULL, caller zeroes it) becomes
+ * max(*amax, max |x[t,:]|) over the tokens with at least one kept assignment.
+ * All other arguments, outputs, limits and errors as moe_permute; H must be a
+ * multiple of 8.
+ */
+moe_status_t moe_permute_fp8(const void* x_bf16, const int32_t* topk_idx, int T, int H, int E, int K,
+                             int capacity, float scale, void* x_perm_fp8, int32_t* expert_counts,
+                             int32_t* expert_offsets, int32_t* row_of_assign, int32_t* assign_of_row,
+                             float* amax, void* workspace, size_t workspace_bytes,
+                             moe_stream_t stream);
+
+/*
  * Grouped SwiGLU expert FFN on E4M3 operands.  x_perm [R_max,H], w_gate, w_up
  * [E,F,H], w_down [E,H,F] are E4M3 codes quantised with scales s_x, s_gate,
  * s_up, s_down.  For every expert over its rows:

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     lib_path,
     max_rows,
     permute,
+    permute_fp8,
     permute_workspace_bytes,
     router_topk,
     set_option,

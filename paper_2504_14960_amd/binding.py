@@ -77,6 +77,8 @@ def lib() -> C.CDLL:
     L.moe_fp8_delayed_scale.argtypes = [C.POINTER(f), i, i]
     L.moe_fp8_quantize.restype = i
     L.moe_fp8_quantize.argtypes = [vp, i, sz, f, vp, vp, vp]
+    L.moe_permute_fp8.restype = i
+    L.moe_permute_fp8.argtypes = [vp, vp, i, i, i, i, i, f, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.moe_grouped_gemm_swiglu_fp8.restype = i
     L.moe_grouped_gemm_swiglu_fp8.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, f, f, f, f, vp, vp, vp, vp]
     L.moe_expert_gate_up_fp8.restype = i
@@ -204,6 +206,19 @@ def fp8_quantize(src: torch.Tensor, scale: float, dst: torch.Tensor, amax: Optio
     if dst.dtype != torch.uint8 or dst.numel() != src.numel():
         raise ValueError("dst must be a uint8 tensor with as many elements as src")
     _check(lib().moe_fp8_quantize(_ptr(src), _dt(src), src.numel(), float(scale), _ptr(dst), _ptr(amax), _stream()))
+
+
+def permute_fp8(x: torch.Tensor, topk_idx: torch.Tensor, E: int, capacity: int, scale: float,
+                x_perm_fp8: torch.Tensor, expert_counts: torch.Tensor, expert_offsets: torch.Tensor,
+                row_of_assign: torch.Tensor, assign_of_row: torch.Tensor, amax: Optional[torch.Tensor],
+                workspace: torch.Tensor) -> None:
+    T, K = topk_idx.shape
+    if x.dtype != torch.bfloat16 or x_perm_fp8.dtype != torch.uint8:
+        raise TypeError("permute_fp8 takes a bf16 x and writes uint8 E4M3 codes")
+    _check(lib().moe_permute_fp8(_ptr(x), _ptr(topk_idx), T, x.shape[1], E, K, int(capacity), float(scale),
+                                 _ptr(x_perm_fp8), _ptr(expert_counts), _ptr(expert_offsets), _ptr(row_of_assign),
+                                 _ptr(assign_of_row), _ptr(amax), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream()))
 
 
 def grouped_gemm_swiglu_fp8(x_perm: torch.Tensor, expert_offsets: torch.Tensor, w_gate: torch.Tensor,

@@ -321,6 +321,39 @@ moe_status_t moe_fp8_quantize(const void* src, moe_dtype_t dt, size_t n, float s
     return check_launch(fn);
 }
 
+moe_status_t moe_permute_fp8(const void* x_bf16, const int32_t* topk_idx, int T, int H, int E, int K,
+                             int capacity, float scale, void* x_perm_fp8, int32_t* expert_counts,
+                             int32_t* expert_offsets, int32_t* row_of_assign, int32_t* assign_of_row,
+                             float* amax, void* workspace, size_t workspace_bytes,
+                             moe_stream_t stream) {
+    static const char* fn = "moe_permute_fp8";
+    if (moe_status_t st = check_dims(fn, T, H, E, K, MOE_BF16)) return st;
+    if (!std::isfinite(scale) || !(scale > 0.f)) return fail(MOE_ERR_INVALID_ARG, "%s: scale must be positive and finite", fn);
+    REQUIRE_PTR(fn, expert_counts);
+    REQUIRE_PTR(fn, expert_offsets);
+    if (T == 0) {
+        launch_fill_i32(expert_counts, E, 0, 0, static_cast<hipStream_t>(stream));
+        launch_fill_i32(expert_offsets, E + 1, 0, 0, static_cast<hipStream_t>(stream));
+        return check_launch(fn);
+    }
+    REQUIRE_PTR(fn, x_bf16);
+    REQUIRE_PTR(fn, x_perm_fp8);
+    REQUIRE_PTR(fn, topk_idx);
+    REQUIRE_PTR(fn, row_of_assign);
+    REQUIRE_PTR(fn, assign_of_row);
+    if (amax && (reinterpret_cast<uintptr_t>(amax) & 3u)) return fail(MOE_ERR_INVALID_ARG, "%s: amax is not 4-byte aligned", fn);
+    const size_t need = permute_workspace_bytes(T, K, E);
+    if (workspace == nullptr || workspace_bytes < need)
+        return fail(MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                    workspace ? workspace_bytes : (size_t)0);
+    REQUIRE_PTR(fn, workspace);
+    const int r_max = moe_max_rows(T, K, E, capacity);
+    launch_permute_fp8(x_bf16, topk_idx, T, H, E, K, capacity, r_max, scale, x_perm_fp8, expert_counts,
+                       expert_offsets, row_of_assign, assign_of_row, amax, workspace,
+                       static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
 static moe_status_t expert_ffn_fp8(const char* fn, int phase, const void* x_perm, const int32_t* expert_offsets,
                                    int R_max, int H, int F, int E, const void* w_gate, const void* w_up,
                                    const void* w_down, float dq_gate, float dq_up, float scale_h, float dq_down,

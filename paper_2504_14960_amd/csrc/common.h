@@ -69,6 +69,9 @@ void launch_fill_i32(int32_t* p, int n, int32_t v0, int32_t step, hipStream_t s)
 void launch_fp8_quantize(const void* src, moe_dtype_t dt, size_t n, float scale, void* dst, float* amax,
                          hipStream_t s);
 bool fp8_ffn_supported(int H, int F);
+void launch_permute_fp8(const void* x, const int32_t* idx, int T, int H, int E, int K, int capacity, int r_max,
+                        float scale, void* x_perm_fp8, int32_t* counts, int32_t* offsets, int32_t* row_of_assign,
+                        int32_t* assign_of_row, float* amax, void* ws, hipStream_t s);
 void launch_expert_ffn_fp8(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                            const void* w_gate, const void* w_up, const void* w_down, float dq_gate, float dq_up,
                            float scale_h, float dq_down, void* h, float* amax_h, void* y_perm, int phase,

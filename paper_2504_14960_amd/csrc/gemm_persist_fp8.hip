@@ -53,15 +53,16 @@ __device__ __forceinline__ float store_h_fp8(f32x16 (&acc)[FM][FN], int t_row0, 
         for (int j = 0; j < FO; ++j) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                uint32_t packed = 0;
+                float hv[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const float g = acc[i][j][4 * q + u] * dq_gate;
                     const float up = acc[i][j + FO][4 * q + u] * dq_up;
-                    const float hv = g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * up;   // silu(g) * up
-                    amax = fmaxf(amax, fabsf(hv));
-                    packed |= f32_to_e4m3(hv * scale_h) << (8 * u);
+                    hv[u] = g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * up;   // silu(g) * up
+                    amax = fmaxf(amax, fabsf(hv[u]));
                 }
+                const uint32_t packed = f32x4_to_e4m3(hv[0] * scale_h, hv[1] * scale_h, hv[2] * scale_h,
+                                                      hv[3] * scale_h);
                 // lane's 4 columns: bytes j*32 + 8q + 4fk .. +3 of the row
                 const int gran = 2 * j + (q >> 1);
                 *reinterpret_cast<uint32_t*>(wrow + ((gran ^ xw) << 4) + 8 * (q & 1)) = packed;
@@ -373,7 +374,8 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
         // rows of the same expert, so they are values h takes anyway.
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
-        if (lane == 0 && amax == amax) atomicMax(reinterpret_cast<int*>(amax_out), __float_as_int(amax));
+        if (lane == 0 && amax > __builtin_nontemporal_load(amax_out))   // *amax_out only grows; NaN compares false
+            atomicMax(reinterpret_cast<int*>(amax_out), __float_as_int(amax));
     }
 }
 

@@ -12,7 +12,7 @@
 //                           with wave ballots and writes both maps.
 //   3. permute_copy_kernel  one wave per token: the row is read once with
 //                           16-byte lanes and stored to each kept destination.
-#include "common.h"
+#include "fp8_convert.h"
 
 namespace moe {
 
@@ -175,6 +175,67 @@ __global__ __launch_bounds__(256) void permute_copy_kernel(const uint8_t* __rest
     }
 }
 
+// Copy fused with FP8 quantisation (Section 4.5 recipe): bf16 rows are read
+// once, scaled, rounded to E4M3 and stored as H bytes to each kept destination;
+// max |x| over the rows that were read is folded into *amax.
+__global__ __launch_bounds__(256) void permute_copy_fp8_kernel(const uint8_t* __restrict__ x,
+                                                               const int32_t* __restrict__ row_of_assign,
+                                                               uint8_t* __restrict__ x_perm, int T, int K, int H,
+                                                               int r_max, float scale, float* __restrict__ amax) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row_bytes = H * 2;
+    float m = 0.f;
+    for (int t = blockIdx.x * 4 + wave; t < T; t += gridDim.x * 4) {
+        int my_row = (lane < K) ? row_of_assign[(size_t)t * K + lane] : -1;
+        if ((unsigned)my_row >= (unsigned)r_max) my_row = -1;
+        const uint64_t kept = __ballot(my_row >= 0);
+        if (!kept) continue;
+        const uint8_t* src = x + (size_t)t * row_bytes;
+        for (int o0 = 0; o0 < row_bytes; o0 += 4096) {  // uniform trip count: shuffles inside
+            const int o = o0 + lane * 16;
+            u32x2 q[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (o + i * 1024 < row_bytes) {
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(src + o + i * 1024);
+                    float f[8];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        f[2 * j] = __uint_as_float(v[j] << 16);
+                        f[2 * j + 1] = __uint_as_float(v[j] & 0xffff0000u);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) m = fmaxf(m, fabsf(f[j]));
+                    q[i][0] = f32x4_to_e4m3(f[0] * scale, f[1] * scale, f[2] * scale, f[3] * scale);
+                    q[i][1] = f32x4_to_e4m3(f[4] * scale, f[5] * scale, f[6] * scale, f[7] * scale);
+                }
+            uint64_t mk = kept;
+            while (mk) {
+                const int k = __ffsll((unsigned long long)mk) - 1;
+                mk &= mk - 1;
+                const int row = __shfl(my_row, k, 64);
+                uint8_t* dst = x_perm + (size_t)row * H + (o >> 1);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (o + i * 1024 < row_bytes) *reinterpret_cast<u32x2*>(dst + i * 512) = q[i];
+            }
+        }
+    }
+    if (amax) {
+        // one atomic per workgroup at most, and none if the value read is already as large
+        // (*amax only grows): atomics on one address serialise
+        __shared__ float wave_max[4];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+        if (lane == 0) wave_max[wave] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            m = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+            if (m > __builtin_nontemporal_load(amax)) atomicMax(reinterpret_cast<int*>(amax), __float_as_int(m));
+        }
+    }
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v0, int32_t step) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v0 + i * step;
@@ -205,6 +266,18 @@ void launch_permute(const void* x, const int32_t* idx, int T, int H, int E, int 
                            static_cast<const uint8_t*>(x), row_of_assign,
                            static_cast<uint8_t*>(x_perm), T, K, row_bytes, r_max);
     }
+}
+
+void launch_permute_fp8(const void* x, const int32_t* idx, int T, int H, int E, int K, int capacity, int r_max,
+                        float scale, void* x_perm_fp8, int32_t* counts, int32_t* offsets, int32_t* row_of_assign,
+                        int32_t* assign_of_row, float* amax, void* ws, hipStream_t s) {
+    // maps as in launch_permute, then the quantising copy
+    launch_permute(nullptr, idx, T, H, E, K, capacity, r_max, MOE_BF16, nullptr, counts, offsets, row_of_assign,
+                   assign_of_row, ws, s);
+    int grid = (T + 3) / 4;
+    if (grid > 256 * 4) grid = 256 * 4;   // few, longer-lived workgroups: fewer amax atomics
+    hipLaunchKernelGGL(permute_copy_fp8_kernel, dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(x),
+                       row_of_assign, static_cast<uint8_t*>(x_perm_fp8), T, K, H, r_max, scale, amax);
 }
 
 void launch_fill_i32(int32_t* p, int n, int32_t v0, int32_t step, hipStream_t s) {

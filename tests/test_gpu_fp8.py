@@ -176,3 +176,34 @@ def test_ffn_fp8_is_reproducible_and_handles_empty_input():
     with pytest.raises(moe.MoeError):
         moe.grouped_gemm_swiglu_fp8(z, off, w, w, wd, 1.0, 1.0, 1.0, 1.0, torch.zeros((8, 256), dtype=torch.uint8, device="cuda"),
                                     None, torch.zeros((8, 192), dtype=torch.bfloat16, device="cuda"))
+
+
+@pytest.mark.parametrize("T,H,E,K,capacity", [(300, 256, 8, 2, 0), (1000, 136, 16, 4, 150), (257, 1032, 64, 8, 0),
+                                              (64, 64, 4, 1, 3)])
+def test_permute_fp8_writes_the_codes_of_the_permuted_rows(T, H, E, K, capacity):
+    import torch
+    import paper_2504_14960_amd as moe
+    rng = np.random.default_rng(T + H)
+    x = make_tokens(6000 + T, T, H, bf16=True)
+    idx = np.stack([rng.permutation(E)[:K] for _ in range(T)]).astype(np.int32)
+    perm = oracle.permute(x, idx, E, capacity)
+    R = perm.R
+    scale = 23.7
+    want_codes, want_amax = oracle.fp8_quantize(perm.x_perm[:R], scale)
+    r_max = moe.max_rows(T, K, E, capacity)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    xq = torch.full((r_max + 3, H), 0xAA, dtype=torch.uint8, device="cuda")
+    counts, offsets = torch.empty((E,), **i32), torch.empty((E + 1,), **i32)
+    roa, aor = torch.empty((T * K,), **i32), torch.empty((r_max,), **i32)
+    ws = torch.empty((moe.permute_workspace_bytes(T, K, E) + 256,), dtype=torch.uint8, device="cuda")
+    amax = torch.zeros(1, dtype=torch.float32, device="cuda")
+    moe.permute_fp8(to_dev(x), to_dev(idx), E, capacity, scale, xq[:r_max], counts, offsets, roa, aor, amax, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(counts.cpu().numpy(), perm.counts)
+    np.testing.assert_array_equal(offsets.cpu().numpy(), perm.offsets)
+    np.testing.assert_array_equal(roa.cpu().numpy(), perm.row_of_assign)
+    np.testing.assert_array_equal(aor.cpu().numpy(), perm.assign_of_row)
+    got = xq.cpu().numpy()
+    np.testing.assert_array_equal(got[:R], want_codes)
+    assert (got[R:] == 0xAA).all()          # rows past the kept ones are untouched
+    assert float(amax.item()) == want_amax
