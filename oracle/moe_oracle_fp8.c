@@ -86,8 +86,9 @@ uint8_t oracle_fp8_encode(float x) {
 /* dst[i] = encode(fp32(src[i] * scale)); *amax = max(*amax, max |src[i]|) */
 void oracle_fp8_quantize(const void* src, int dt, size_t n, float scale, uint8_t* dst, float* amax) {
     float m = amax ? *amax : 0.0f;
-    for (size_t i = 0; i < n; ++i) {
-        float v = ldf(src, i, dt);
+#pragma omp parallel for schedule(static) reduction(max : m)
+    for (long long i = 0; i < (long long)n; ++i) {
+        float v = ldf(src, (size_t)i, dt);
         volatile float p = v * scale;   /* one fp32 rounding, never contracted or widened */
         dst[i] = oracle_fp8_encode(p);
         float av = fabsf(v);

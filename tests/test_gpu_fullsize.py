@@ -134,3 +134,94 @@ def test_full_size_layer(name):
         y = values(to_host(o["y"]))
         assert (y[~kept_any] == 0).all()
         assert np.isfinite(y).all()
+
+
+@pytest.mark.parametrize("name", ["mixtral8x22b", "tokendrop"])
+def test_full_size_fp8_expert_ffn(name):
+    """The FP8 chain bench.py --precision fp8 times (permute fused with quantisation, the two FP8 grouped GEMMs,
+    combine), at full size: maps and the E4M3 codes of every kept row in full, FFN rows and layer outputs on
+    sampled tokens against the FP8 oracle."""
+    import torch
+    import paper_2504_14960_amd as moe
+    cfg = get_config(name)
+    T, H, E, K, F = cfg.T, cfg.H, cfg.E, cfg.K, cfg.F
+    inp = make_layer_inputs(cfg)
+    guard_margins(inp, K)
+    capacity = capacity_rows(cfg)
+    t = inp.tensors
+    l64 = oracle.router_logits(t["x"], t["w_router"], inp.bias)
+    want_idx, want_gate = oracle.topk_gates(l64.astype(np.float32), K, cfg.renormalize)
+    perm = oracle.permute(None, want_idx, E, capacity)
+    R = perm.R
+    token_of_row = perm.assign_of_row[:R] // K
+
+    # scales as a delayed-scaling run would hold them: from amax values slightly above today's
+    sc, wq = {}, {}
+    for k in ("w_gate", "w_up", "w_down"):
+        sc[k] = oracle.fp8_delayed_scale([oracle.fp8_quantize(t[k], 1.0)[1] * 1.05])
+        wq[k] = oracle.fp8_quantize(t[k], sc[k])[0]
+    sc["x"] = oracle.fp8_delayed_scale([oracle.fp8_quantize(t["x"], 1.0)[1] * 1.05])
+    dq_gate, dq_up = 1.0 / (sc["x"] * sc["w_gate"]), 1.0 / (sc["x"] * sc["w_up"])
+
+    # sampled tokens and their kept rows, grouped by expert for the oracle
+    rng = np.random.default_rng(cfg.seed + 1)
+    kept_any = (perm.row_of_assign.reshape(T, K) >= 0).any(axis=1)
+    pool = np.nonzero(kept_any)[0]
+    tokens = np.sort(rng.choice(pool, size=min(N_SAMPLE_TOKENS, pool.size), replace=False))
+    rows = np.unique(perm.row_of_assign.reshape(T, K)[tokens].reshape(-1))
+    rows = rows[rows >= 0]                                  # ascending = grouped by expert
+    expert_of_row = np.searchsorted(perm.offsets, rows, side="right") - 1
+    sub_offsets = np.concatenate([[0], np.cumsum(np.bincount(expert_of_row, minlength=E))]).astype(np.int32)
+    xq_rows = oracle.fp8_quantize(np.ascontiguousarray(t["x"][token_of_row[rows]]), sc["x"])[0]
+    probe = oracle.experts_fp8(xq_rows, sub_offsets, wq["w_gate"], wq["w_up"], wq["w_down"], dq_gate, dq_up, 1.0, 1.0)
+    scale_h = oracle.fp8_delayed_scale([probe.amax_h * 1.5])
+    dq_down = 1.0 / (scale_h * sc["w_down"])
+    ref = oracle.experts_fp8(xq_rows, sub_offsets, wq["w_gate"], wq["w_up"], wq["w_down"], dq_gate, dq_up, scale_h,
+                             dq_down)
+
+    # ---- GPU: the stage calls of the FP8 bench ----
+    r_max = moe.max_rows(T, K, E, capacity)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_x, d_idx, d_gate = to_dev(t["x"]), to_dev(want_idx), to_dev(want_gate.astype(np.float32))
+    counts, offsets = torch.empty((E,), **i32), torch.empty((E + 1,), **i32)
+    roa, aor = torch.empty((T * K,), **i32), torch.empty((r_max,), **i32)
+    pws = torch.empty((moe.permute_workspace_bytes(T, K, E) + 256,), dtype=torch.uint8, device="cuda")
+    xq = torch.zeros((r_max, H), dtype=torch.uint8, device="cuda")
+    hq = torch.zeros((r_max, F), dtype=torch.uint8, device="cuda")
+    y_perm = torch.zeros((r_max, H), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
+    amax = torch.zeros(2, dtype=torch.float32, device="cuda")
+    dwq = {k: torch.from_numpy(v).cuda() for k, v in wq.items()}
+    moe.permute_fp8(d_x, d_idx, E, capacity, sc["x"], xq, counts, offsets, roa, aor, amax[0:1], pws)
+    moe.expert_gate_up_fp8(xq, offsets, dwq["w_gate"], dwq["w_up"], dq_gate, dq_up, scale_h, hq, amax[1:2])
+    moe.expert_down_fp8(hq, offsets, dwq["w_down"], dq_down, y_perm)
+    moe.unpermute_combine(y_perm, roa, d_gate, None, y)
+    torch.cuda.synchronize()
+
+    # maps and every kept row's codes, in full
+    np.testing.assert_array_equal(to_host(offsets), perm.offsets)
+    np.testing.assert_array_equal(to_host(roa), perm.row_of_assign)
+    got_xq = xq.cpu().numpy()
+    step = 4096
+    for lo in range(0, R, step):                            # in slices: the oracle quantises on one core
+        hi = min(R, lo + step)
+        want = oracle.fp8_quantize(np.ascontiguousarray(t["x"][token_of_row[lo:hi]]), sc["x"])[0]
+        np.testing.assert_array_equal(got_xq[lo:hi], want)
+    kept_tokens = np.unique(token_of_row)
+    assert float(amax[0].item()) == float(np.abs(values(t["x"][kept_tokens])).max())
+
+    # sampled rows: h codes and y_perm; sampled tokens: y
+    dev_rows = torch.from_numpy(rows.astype(np.int64)).cuda()
+    got_h = hq[dev_rows].cpu().numpy()
+    differ = got_h != ref.hq
+    assert differ.mean() <= 3e-3
+    gv, rv = oracle.fp8_decode(got_h[differ]), oracle.fp8_decode(ref.hq[differ])
+    assert (np.abs(gv - rv) <= np.maximum(np.abs(rv) * 2.0 ** -3, 2.0 ** -9)).all()
+    assert float(amax[1].item()) >= ref.amax_h * (1 - 1e-5)  # the sample's maximum is a lower bound of the tensor's
+    assert_close(to_host(y_perm[dev_rows]), ref.y, True, f"fp8 y_perm rows ({name})")
+    remap = {int(r): i for i, r in enumerate(rows)}
+    roa_s = np.array([[remap[int(r)] if r >= 0 else -1 for r in perm.row_of_assign.reshape(T, K)[tk]] for tk in tokens],
+                     dtype=np.int32)
+    y_ref = oracle.combine(ref.y, roa_s.reshape(-1), want_gate[tokens], None)
+    dev_tok = torch.from_numpy(tokens.astype(np.int64)).cuda()
+    assert_close(to_host(y[dev_tok]), y_ref, True, f"fp8 y rows ({name})")
