@@ -88,3 +88,11 @@ def test_product_package_does_not_import_the_oracle():
             if fn.endswith((".py", ".hip", ".h")):
                 src = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in src.lower(), f"{fn} mentions the oracle"
+
+
+def test_fp8_delayed_scale_closed_forms():
+    assert moe.fp8_delayed_scale([1.0, 2.0, 0.5]) == 224.0            # 448 / largest amax
+    assert moe.fp8_delayed_scale([1.0, 2.0, 0.5], 1) == 112.0         # one power of two of headroom
+    assert moe.fp8_delayed_scale([0.0, 0.0]) == 1.0 and moe.fp8_delayed_scale([]) == 1.0   # nothing recorded yet
+    assert moe.fp8_delayed_scale([float("inf"), 4.0]) == 112.0        # non-finite entries ignored
+    assert moe.fp8_delayed_scale([float("nan"), 8.0]) == 56.0
