@@ -272,7 +272,8 @@ moe_status_t moe_expert_down_fp8(const void* h_fp8, const int32_t* expert_offset
  * the tuned ones).  Unknown names return MOE_ERR_INVALID_ARG.  Names:
  * "gemm_variant" (0 = auto); "gemm_workgroups" (workgroups launched by the
  * persistent grouped-GEMM kernels; 0 = one per compute unit, values below 8
- * are raised to 8). */
+ * are raised to 8); "router_tile" (16-token blocks per router workgroup: 1, 2
+ * or 4; 0 = chosen from T and E). */
 moe_status_t moe_set_option(const char* name, int value);
 
 #ifdef __cplusplus

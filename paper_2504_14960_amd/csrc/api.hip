@@ -410,6 +410,12 @@ moe_status_t moe_expert_down_fp8(const void* h_fp8, const int32_t* expert_offset
 }
 
 moe_status_t moe_set_option(const char* name, int value) {
+    if (name && strcmp(name, "router_tile") == 0) {
+        if (value != 0 && value != 1 && value != 2 && value != 4)
+            return fail(MOE_ERR_INVALID_ARG, "moe_set_option: router_tile must be 0, 1, 2 or 4");
+        moe::set_router_tile(value);
+        return MOE_OK;
+    }
     if (name && strcmp(name, "gemm_workgroups") == 0) {
         if (value < 0) return fail(MOE_ERR_INVALID_ARG, "moe_set_option: gemm_workgroups must be >= 0");
         moe::set_persist_workgroups(value);

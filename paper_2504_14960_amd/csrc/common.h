@@ -44,6 +44,9 @@ void launch_router(const void* x, const void* w, const float* bias, float* logit
                    int E, int K, int renorm, moe_dtype_t dt, int32_t* idx, float* gate,
                    hipStream_t s);
 
+// router: 16-token blocks per workgroup (1, 2 or 4); 0 = chosen from T and E
+void set_router_tile(int mb);
+
 size_t permute_workspace_bytes(int T, int K, int E);
 void launch_permute(const void* x, const int32_t* idx, int T, int H, int E, int K, int capacity,
                     int r_max, moe_dtype_t dt, void* x_perm, int32_t* counts, int32_t* offsets,

@@ -56,12 +56,23 @@ __global__ __launch_bounds__(256) void permute_map_kernel(
     base[tid] = 0;
     for (int i = tid; i < kUnits * kMaxExperts; i += 256) (&unit_cnt[0][0])[i] = 0;
     __syncthreads();
-    for (int i = tid; i < nchunks * E; i += 256) {
-        const int c = i / E, e = i - c * E;
-        const int v = chunk_hist[i];
-        if (v) {
-            atomicAdd(&tot[e], v);
-            if (c < chunk) atomicAdd(&base[e], v);
+    {
+        // per-expert totals over all chunks and over the chunks before this one.  Thread
+        // (cs, e) sums every `groups`-th chunk privately (independent loads, so many are in
+        // flight), then adds its two partial sums to the shared cells once.
+        int ep = 1;
+        while (ep < E) ep <<= 1;
+        const int groups = 256 / ep, cs = tid / ep, e = tid % ep;
+        if (e < E) {
+            int t_sum = 0, b_sum = 0;
+#pragma unroll 8
+            for (int c = cs; c < nchunks; c += groups) {
+                const int v = chunk_hist[(size_t)c * E + e];
+                t_sum += v;
+                b_sum += (c < chunk) ? v : 0;
+            }
+            if (t_sum) atomicAdd(&tot[e], t_sum);
+            if (b_sum) atomicAdd(&base[e], b_sum);
         }
     }
     __syncthreads();

@@ -439,6 +439,9 @@ void launch_bf16(const void* x, const void* w, const float* bias, float* logits,
 
 }  // namespace
 
+static int g_router_tile = 0;  // 16-token blocks per workgroup; 0 = chosen from T and E
+void set_router_tile(int mb) { g_router_tile = mb; }
+
 void launch_router(const void* x, const void* w, const float* bias, float* logits, int T, int H,
                    int E, int K, int renorm, moe_dtype_t dt, int32_t* idx, float* gate,
                    hipStream_t s) {
@@ -460,6 +463,7 @@ void launch_router(const void* x, const void* w, const float* bias, float* logit
     // experts a taller tile so the router weight is re-read less often
     int mb = (T >= 32768) ? 4 : (T >= 16384 ? 2 : 1);
     if (nb >= 4 && mb < 2) mb = 2;
+    if (g_router_tile == 1 || g_router_tile == 2 || g_router_tile == 4) mb = g_router_tile;
 #define ROUTER_CASE(M, N)                                                          \
     launch_bf16<M, N>(x, w, bias, logits, T, H, E, K, renorm, idx, gate, s);       \
     return;
@@ -468,7 +472,7 @@ void launch_router(const void* x, const void* w, const float* bias, float* logit
     } else if (nb <= 2) {
         if (mb == 4) { ROUTER_CASE(4, 2) } else if (mb == 2) { ROUTER_CASE(2, 2) } else { ROUTER_CASE(1, 2) }
     } else if (nb <= 4) {
-        if (mb == 4) { ROUTER_CASE(4, 4) } else { ROUTER_CASE(2, 4) }
+        if (mb == 4) { ROUTER_CASE(4, 4) } else if (mb == 2) { ROUTER_CASE(2, 4) } else { ROUTER_CASE(1, 4) }
     } else if (nb <= 8) {
         ROUTER_CASE(2, 8)
     } else {
