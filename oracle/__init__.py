@@ -170,6 +170,38 @@ def combine(y_perm: np.ndarray, row_of_assign: np.ndarray, gate: np.ndarray,
     return y
 
 
+def combine_backward(dy: np.ndarray, y_perm: np.ndarray, row_of_assign: np.ndarray, gate: np.ndarray):
+    """Backward of combine(): returns (dy_perm [R,H], dgate [T,K]); rows of dy_perm that no kept
+    assignment points at stay zero."""
+    dy = np.ascontiguousarray(dy, dtype=np.float64)
+    y_perm = np.ascontiguousarray(y_perm, dtype=np.float64)
+    gate = np.ascontiguousarray(gate, dtype=np.float64)
+    T, K = gate.shape
+    H = dy.shape[1]
+    roa = np.ascontiguousarray(row_of_assign, dtype=np.int32).reshape(-1)
+    assert roa.size == T * K and dy.shape == (T, H) and y_perm.shape[1] == H
+    assert roa.max(initial=-1) < y_perm.shape[0]
+    dy_perm = np.zeros_like(y_perm)
+    dgate = np.zeros((T, K), dtype=np.float64)
+    lib().oracle_combine_backward(_p(dy), _p(y_perm), _p(roa), _p(gate), T, H, K, _p(dy_perm), _p(dgate))
+    return dy_perm, dgate
+
+
+def permute_backward(dx_perm: np.ndarray, row_of_assign: np.ndarray, T: int, K: int,
+                     addend: Optional[np.ndarray] = None) -> np.ndarray:
+    """Backward of permute(): dx [T,H]."""
+    dx_perm = np.ascontiguousarray(dx_perm, dtype=np.float64)
+    H = dx_perm.shape[1]
+    roa = np.ascontiguousarray(row_of_assign, dtype=np.int32).reshape(-1)
+    assert roa.size == T * K and roa.max(initial=-1) < dx_perm.shape[0]
+    if addend is not None:
+        addend = np.ascontiguousarray(addend, dtype=np.float64)
+        assert addend.shape == (T, H)
+    dx = np.zeros((T, H), dtype=np.float64)
+    lib().oracle_permute_backward(_p(dx_perm), _p(roa), _p(addend), T, H, K, _p(dx))
+    return dx
+
+
 class LayerResult:
     def __init__(self, R, logits32, idx, gate, row_of_assign, y):
         self.R = R

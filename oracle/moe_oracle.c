@@ -43,7 +43,9 @@
  * gates sum to 1, capacity values), E = 1 reduces to a dense MLP computed with
  * a library matmul, stable argsort cross-check of the permutation, identity
  * experts give permute/unpermute round trip, brute-force dense Eq. 1 below,
- * batch-split invariance, dropped-tokens-are-zero.  No function here is
+ * batch-split invariance, dropped-tokens-are-zero; the two backward functions by
+ * the adjoint identity <F(a), b> = <a, F'(b)> on random tensors, finite
+ * differences in the gates, and a library scatter-add.  No function here is
  * "parity unpinned"; the paper prints no worked numeric example of the layer.
  */
 #include <math.h>
@@ -262,6 +264,48 @@ void oracle_combine(const double* y_perm, const int32_t* row_of_assign, const do
             }
             if (addend) acc += addend[(size_t)t * H + n];
             y[(size_t)t * H + n] = acc;
+        }
+}
+
+/* ---- backward of the dispatcher's two data movements (Section 3.3: the
+ * backward workflow mirrors the forward one) ----
+ *
+ * "Token Restore" + weighted sum, y[t,:] = sum_k gate[t,k] * y_perm[row(t,k),:]:
+ *   dy_perm[row(t,k),:] = gate[t,k] * dy[t,:]        (every kept row has one source)
+ *   dgate[t,k]          = sum_n dy[t,n] * y_perm[row(t,k),n]   (0 for a dropped assignment)
+ * dy_perm [R,H] is written for kept rows only (rows are hit exactly once). */
+void oracle_combine_backward(const double* dy, const double* y_perm, const int32_t* row_of_assign,
+                             const double* gate, int T, int H, int K, double* dy_perm, double* dgate) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t)
+        for (int k = 0; k < K; ++k) {
+            size_t a = (size_t)t * K + k;
+            int row = row_of_assign[a];
+            double dot = 0.0;
+            if (row >= 0)
+                for (int n = 0; n < H; ++n) {
+                    dy_perm[(size_t)row * H + n] = gate[a] * dy[(size_t)t * H + n];
+                    dot += dy[(size_t)t * H + n] * y_perm[(size_t)row * H + n];
+                }
+            dgate[a] = dot;
+        }
+}
+
+/* "Token Dispatching", x_perm[row(t,k),:] = x[t,:] for kept assignments:
+ *   dx[t,:] = sum over kept k of dx_perm[row(t,k),:]  (+ addend[t,:], the gradient that
+ *   reaches x along other paths) */
+void oracle_permute_backward(const double* dx_perm, const int32_t* row_of_assign, const double* addend,
+                             int T, int H, int K, double* dx) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t)
+        for (int n = 0; n < H; ++n) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) {
+                int row = row_of_assign[(size_t)t * K + k];
+                if (row >= 0) acc += dx_perm[(size_t)row * H + n];
+            }
+            if (addend) acc += addend[(size_t)t * H + n];
+            dx[(size_t)t * H + n] = acc;
         }
 }
 
