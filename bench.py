@@ -44,6 +44,9 @@ def parse_args():
                     help="fp8: expert FFN on E4M3 operands with delayed per-tensor scaling (weights quantised "
                          "beforehand and resident, activations quantised inside the timed step); a separate "
                          "experiment, the headline metric is the bf16 run")
+    ap.add_argument("--dispatch-backward", action="store_true",
+                    help="also time the backward of the dispatcher's two data movements (combine backward, permute "
+                         "backward) on the same routing; reported in a separate object, not part of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -300,6 +303,31 @@ def main():
         "context": "the paper reports 49.3 % (Mixtral 8x22B) and 39.0 % (Qwen2-57B-A14B) MFU for whole training "
                    "steps on H100 clusters: other hardware, other scope, shown for orientation only",
     }
+    if args.dispatch_backward and not fp8:
+        # dy plays the gradient of the layer output; the forward's y_perm, maps and gates are reused
+        res = {}
+        dgs = [torch.empty((T, K), dtype=torch.float32, device="cuda") for _ in sets]
+        def cb(i):
+            s = sets[i % NSETS]
+            moe.unpermute_combine_backward(s["y"], s["y_perm"], s["roa"], s["gate"], s["x_perm"], dgs[i % NSETS])
+        def pb(i):
+            s = sets[i % NSETS]
+            moe.permute_backward(s["x_perm"], s["roa"], None, s["y"], K)
+        for nm, fn, work in (("combine_backward", cb, (T + 2 * R) * H * es + 12 * T * K),
+                             ("permute_backward", pb, (R + T) * H * es + 4 * T * K)):
+            for i in range(args.warmup):
+                fn(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(args.steps):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            rate = work / (ms * 1e-3) / 1e9
+            res[nm] = {"ms": round(ms, 4), "achieved": round(rate, 1), "unit": "GB/s", "frac": round(rate / PEAK_HBM_GBS, 4)}
+        out["dispatch_backward"] = res
     if not args.no_cpu_baseline and not fp8:
         out["cpu_baseline"] = cpu_baseline(inp, capacity, args.cpu_seconds)
     print(json.dumps(out))

@@ -171,6 +171,31 @@ moe_status_t moe_unpermute_combine(const void* y_perm, const int32_t* row_of_ass
                                    const float* topk_gate, const void* addend, int T, int H,
                                    int K, int R_max, moe_dtype_t dt, void* y, moe_stream_t stream);
 
+/*
+ * Backward of the dispatcher's two data movements (Section 3.3: the backward
+ * workflow mirrors the forward one).
+ *
+ * moe_unpermute_combine_backward, for y = moe_unpermute_combine(y_perm, ...):
+ *   dy_perm[row_of_assign[t*K+k],:] = topk_gate[t,k] * dy[t,:]      (rounded to dt once)
+ *   dgate[t,k] = sum_n dy[t,n] * y_perm[row_of_assign[t*K+k],n]     (fp32; 0 if dropped)
+ * dy [T,H], y_perm [R_max,H] (the forward's), dy_perm [R_max,H] (dt; only rows
+ * some kept assignment points at are written), dgate [T,K] fp32.
+ *
+ * moe_permute_backward, for x_perm = moe_permute(x, ...):
+ *   dx[t,:] = sum over kept k of dx_perm[row_of_assign[t*K+k],:]  (+ addend[t,:])
+ * accumulated in fp32 and rounded to dt once; addend [T,H] (dt) or NULL carries
+ * the gradient that reaches x along other paths (router, residual).
+ *
+ * Limits and errors as moe_unpermute_combine.
+ */
+moe_status_t moe_unpermute_combine_backward(const void* dy, const void* y_perm,
+                                            const int32_t* row_of_assign, const float* topk_gate,
+                                            int T, int H, int K, int R_max, moe_dtype_t dt,
+                                            void* dy_perm, float* dgate, moe_stream_t stream);
+moe_status_t moe_permute_backward(const void* dx_perm, const int32_t* row_of_assign,
+                                  const void* addend, int T, int H, int K, int R_max,
+                                  moe_dtype_t dt, void* dx, moe_stream_t stream);
+
 /* Bytes of workspace moe_layer_forward needs.  Fs = FFN size of the shared
  * expert (0 = none).  Host only. */
 size_t moe_layer_workspace_bytes(int T, int H, int E, int K, int F, int Fs, int capacity,

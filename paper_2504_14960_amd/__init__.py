@@ -24,10 +24,12 @@ from .binding import (  # noqa: F401
     lib_path,
     max_rows,
     permute,
+    permute_backward,
     permute_fp8,
     permute_workspace_bytes,
     router_topk,
     set_option,
     unpermute_combine,
+    unpermute_combine_backward,
     version,
 )

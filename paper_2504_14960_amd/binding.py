@@ -64,6 +64,10 @@ def lib() -> C.CDLL:
     L.moe_expert_down.argtypes = [vp, vp, i, i, i, i, vp, i, vp, vp]
     L.moe_unpermute_combine.restype = i
     L.moe_unpermute_combine.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, vp]
+    L.moe_unpermute_combine_backward.restype = i
+    L.moe_unpermute_combine_backward.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, vp, vp]
+    L.moe_permute_backward.restype = i
+    L.moe_permute_backward.argtypes = [vp, vp, vp, i, i, i, i, i, vp, vp]
     L.moe_layer_workspace_bytes.restype = sz
     L.moe_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
     L.moe_layer_workspace_layout.restype = i
@@ -248,6 +252,21 @@ def expert_down_fp8(h: torch.Tensor, expert_offsets: torch.Tensor, w_down: torch
     E, H, _ = w_down.shape
     _check(lib().moe_expert_down_fp8(_ptr(h), _ptr(expert_offsets), R_max, H, F, E, _ptr(w_down), float(dq_down),
                                      _ptr(y_perm), _stream()))
+
+
+def unpermute_combine_backward(dy: torch.Tensor, y_perm: torch.Tensor, row_of_assign: torch.Tensor,
+                               topk_gate: torch.Tensor, dy_perm: torch.Tensor, dgate: torch.Tensor) -> None:
+    T, K = topk_gate.shape
+    R_max, H = y_perm.shape
+    _check(lib().moe_unpermute_combine_backward(_ptr(dy), _ptr(y_perm), _ptr(row_of_assign), _ptr(topk_gate), T, H, K,
+                                                R_max, _dt(dy), _ptr(dy_perm), _ptr(dgate), _stream()))
+
+
+def permute_backward(dx_perm: torch.Tensor, row_of_assign: torch.Tensor, addend: Optional[torch.Tensor],
+                     dx: torch.Tensor, K: int) -> None:
+    T, H = dx.shape
+    _check(lib().moe_permute_backward(_ptr(dx_perm), _ptr(row_of_assign), _ptr(addend), T, H, K, dx_perm.shape[0],
+                                      _dt(dx), _ptr(dx), _stream()))
 
 
 def layer_workspace_bytes(T: int, H: int, E: int, K: int, F: int, Fs: int, capacity: int, dtype: int) -> int:

@@ -235,6 +235,43 @@ moe_status_t moe_unpermute_combine(const void* y_perm, const int32_t* row_of_ass
     return check_launch(fn);
 }
 
+moe_status_t moe_unpermute_combine_backward(const void* dy, const void* y_perm,
+                                            const int32_t* row_of_assign, const float* topk_gate,
+                                            int T, int H, int K, int R_max, moe_dtype_t dt,
+                                            void* dy_perm, float* dgate, moe_stream_t stream) {
+    static const char* fn = "moe_unpermute_combine_backward";
+    if (moe_status_t st = check_dims(fn, T, H, K, K, dt)) return st;
+    if (R_max < 0) return fail(MOE_ERR_INVALID_ARG, "%s: R_max=%d is negative", fn, R_max);
+    if (T == 0) return MOE_OK;
+    REQUIRE_PTR(fn, dy);
+    REQUIRE_PTR(fn, row_of_assign);
+    REQUIRE_PTR(fn, topk_gate);
+    REQUIRE_PTR(fn, dgate);
+    if (R_max > 0) {
+        REQUIRE_PTR(fn, y_perm);
+        REQUIRE_PTR(fn, dy_perm);
+    }
+    launch_combine_backward(dy, y_perm, row_of_assign, topk_gate, T, H, K, R_max, dt, dy_perm, dgate,
+                            static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
+moe_status_t moe_permute_backward(const void* dx_perm, const int32_t* row_of_assign,
+                                  const void* addend, int T, int H, int K, int R_max,
+                                  moe_dtype_t dt, void* dx, moe_stream_t stream) {
+    static const char* fn = "moe_permute_backward";
+    if (moe_status_t st = check_dims(fn, T, H, K, K, dt)) return st;
+    if (R_max < 0) return fail(MOE_ERR_INVALID_ARG, "%s: R_max=%d is negative", fn, R_max);
+    if (T == 0) return MOE_OK;
+    REQUIRE_PTR(fn, row_of_assign);
+    REQUIRE_PTR(fn, dx);
+    if (R_max > 0) REQUIRE_PTR(fn, dx_perm);
+    if (addend && !aligned16(addend)) return fail(MOE_ERR_INVALID_ARG, "%s: addend is not 16-byte aligned", fn);
+    // the sum of the kept rows of every token: the combine without gates
+    launch_combine(dx_perm, row_of_assign, nullptr, addend, T, H, K, R_max, dt, dx, static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
 size_t moe_layer_workspace_bytes(int T, int H, int E, int K, int F, int Fs, int capacity,
                                  moe_dtype_t dt) {
     if (T < 0 || H <= 0 || E <= 0 || K <= 0 || F <= 0 || Fs < 0) return 0;

@@ -56,6 +56,10 @@ void launch_combine(const void* y_perm, const int32_t* row_of_assign, const floa
                     const void* addend, int T, int H, int K, int r_max, moe_dtype_t dt, void* y,
                     hipStream_t s);
 
+void launch_combine_backward(const void* dy, const void* y_perm, const int32_t* row_of_assign, const float* gate,
+                             int T, int H, int K, int r_max, moe_dtype_t dt, void* dy_perm, float* dgate,
+                             hipStream_t s);
+
 // persistent grouped-GEMM kernels: workgroups per launch, 0 = one per compute unit
 void set_persist_workgroups(int n);
 
