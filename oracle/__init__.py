@@ -170,6 +170,27 @@ def combine(y_perm: np.ndarray, row_of_assign: np.ndarray, gate: np.ndarray,
     return y
 
 
+def experts_backward(x_perm: np.ndarray, offsets: np.ndarray, w_gate: np.ndarray, w_up: np.ndarray,
+                     w_down: np.ndarray, dy: np.ndarray):
+    """Backward of experts(): returns (dx [R,H], dw_gate [E,F,H], dw_up [E,F,H], dw_down [E,H,F]) in double."""
+    E, F, H = w_gate.shape
+    assert w_up.shape == (E, F, H) and w_down.shape == (E, H, F)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+    R = int(offsets[E])
+    assert x_perm.shape[0] >= R and x_perm.shape[1] == H
+    dt = _dt(x_perm)
+    assert dt == _dt(w_gate) == _dt(w_up) == _dt(w_down)
+    dy = np.ascontiguousarray(dy, dtype=np.float64)
+    assert dy.shape[0] >= R and dy.shape[1] == H
+    dx = np.zeros((R, H), dtype=np.float64)
+    dwg = np.zeros((E, F, H), dtype=np.float64)
+    dwu = np.zeros((E, F, H), dtype=np.float64)
+    dwd = np.zeros((E, H, F), dtype=np.float64)
+    lib().oracle_experts_backward(_p(np.ascontiguousarray(x_perm)), _p(offsets), E, H, F, _p(w_gate), _p(w_up),
+                                  _p(w_down), dt, _p(dy), _p(dx), _p(dwg), _p(dwu), _p(dwd))
+    return dx, dwg, dwu, dwd
+
+
 def combine_backward(dy: np.ndarray, y_perm: np.ndarray, row_of_assign: np.ndarray, gate: np.ndarray):
     """Backward of combine(): returns (dy_perm [R,H], dgate [T,K]); rows of dy_perm that no kept
     assignment points at stay zero."""

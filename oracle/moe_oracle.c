@@ -248,6 +248,94 @@ void oracle_experts(const void* x_perm, const int32_t* offsets, int E, int H, in
     }
 }
 
+/* ---- backward of "Expert Computation" (Section 3.3: the backward workflow mirrors
+ * the forward one; f_e of Eq. 1 differentiated by the chain rule) ----
+ * For every expert e over its rows r, with g = x W_gate^T, u = x W_up^T,
+ * s = 1 / (1 + exp(-g)), h = g s u, y = h W_down^T and dy given:
+ *   dW_down[e][n][f] = sum_r dy[r,n] h[r,f]
+ *   dh[r,f]          = sum_n dy[r,n] W_down[e][n][f]
+ *   du[r,f]          = dh[r,f] g s                      (d h / d u = silu(g))
+ *   dg[r,f]          = dh[r,f] u s (1 + g (1 - s))      (d silu / d g = s (1 + g (1 - s)))
+ *   dW_gate[e][f][k] = sum_r dg[r,f] x[r,k],  dW_up[e][f][k] = sum_r du[r,f] x[r,k]
+ *   dx[r,k]          = sum_f dg[r,f] W_gate[e][f][k] + du[r,f] W_up[e][f][k]
+ * dy [R,H] double; x_perm and the weights in dt.  Outputs (double): dx [R,H],
+ * dw_gate, dw_up [E,F,H], dw_down [E,H,F] (experts without rows get zeros). */
+void oracle_experts_backward(const void* x_perm, const int32_t* offsets, int E, int H, int F,
+                             const void* w_gate, const void* w_up, const void* w_down, int dt,
+                             const double* dy, double* dx, double* dw_gate, double* dw_up,
+                             double* dw_down) {
+    memset(dw_gate, 0, sizeof(double) * (size_t)E * F * H);
+    memset(dw_up, 0, sizeof(double) * (size_t)E * F * H);
+    memset(dw_down, 0, sizeof(double) * (size_t)E * H * F);
+    for (int e = 0; e < E; ++e) {
+        const int lo = offsets[e], hi = offsets[e + 1], n_rows = hi - lo;
+        if (n_rows <= 0) continue;
+        const size_t wo = (size_t)e * F * H;
+        double* g = (double*)malloc(sizeof(double) * (size_t)n_rows * F);
+        double* u = (double*)malloc(sizeof(double) * (size_t)n_rows * F);
+        double* dg = (double*)malloc(sizeof(double) * (size_t)n_rows * F);
+        double* du = (double*)malloc(sizeof(double) * (size_t)n_rows * F);
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int r = 0; r < n_rows; ++r)
+            for (int f = 0; f < F; ++f) {
+                double gs = 0.0, us = 0.0;
+                for (int k = 0; k < H; ++k) {
+                    double xv = ld(x_perm, (size_t)(lo + r) * H + k, dt);
+                    gs += xv * ld(w_gate, wo + (size_t)f * H + k, dt);
+                    us += xv * ld(w_up, wo + (size_t)f * H + k, dt);
+                }
+                g[(size_t)r * F + f] = gs;
+                u[(size_t)r * F + f] = us;
+            }
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int r = 0; r < n_rows; ++r)
+            for (int f = 0; f < F; ++f) {
+                double dh = 0.0;
+                for (int n = 0; n < H; ++n)
+                    dh += dy[(size_t)(lo + r) * H + n] * ld(w_down, wo + (size_t)n * F + f, dt);
+                double gv = g[(size_t)r * F + f], uv = u[(size_t)r * F + f];
+                double sg = 1.0 / (1.0 + exp(-gv));
+                du[(size_t)r * F + f] = dh * gv * sg;
+                dg[(size_t)r * F + f] = dh * uv * sg * (1.0 + gv * (1.0 - sg));
+            }
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int n = 0; n < H; ++n)
+            for (int f = 0; f < F; ++f) {
+                double acc = 0.0;
+                for (int r = 0; r < n_rows; ++r) {
+                    double gv = g[(size_t)r * F + f], uv = u[(size_t)r * F + f];
+                    acc += dy[(size_t)(lo + r) * H + n] * (gv / (1.0 + exp(-gv)) * uv);
+                }
+                dw_down[wo + (size_t)n * F + f] = acc;
+            }
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int f = 0; f < F; ++f)
+            for (int k = 0; k < H; ++k) {
+                double ag = 0.0, au = 0.0;
+                for (int r = 0; r < n_rows; ++r) {
+                    double xv = ld(x_perm, (size_t)(lo + r) * H + k, dt);
+                    ag += dg[(size_t)r * F + f] * xv;
+                    au += du[(size_t)r * F + f] * xv;
+                }
+                dw_gate[wo + (size_t)f * H + k] = ag;
+                dw_up[wo + (size_t)f * H + k] = au;
+            }
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int r = 0; r < n_rows; ++r)
+            for (int k = 0; k < H; ++k) {
+                double acc = 0.0;
+                for (int f = 0; f < F; ++f)
+                    acc += dg[(size_t)r * F + f] * ld(w_gate, wo + (size_t)f * H + k, dt) +
+                           du[(size_t)r * F + f] * ld(w_up, wo + (size_t)f * H + k, dt);
+                dx[(size_t)(lo + r) * H + k] = acc;
+            }
+        free(g);
+        free(u);
+        free(dg);
+        free(du);
+    }
+}
+
 /* ---- "Token Restore" + Eq. 1's weighted sum ----
  * y[t,:] = sum over k ascending of gate[t,k] * y_perm[row_of_assign[t,k],:]
  * (dropped assignments contribute nothing) (+ addend[t,:]). */

@@ -75,3 +75,48 @@ def test_backward_of_the_round_trip_with_unit_gates_counts_kept_copies():
     dx = oracle.permute_backward(dy_perm, perm.row_of_assign, T, K)
     kept = (perm.row_of_assign.reshape(T, K) >= 0).sum(axis=1)
     np.testing.assert_allclose(dx, kept[:, None] * dy, rtol=1e-15)
+
+
+def _ffn_case(seed, E, H, F, counts):
+    rng = np.random.default_rng(seed)
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R = int(offsets[-1])
+    x = rng.normal(0, 1, (R, H)).astype(np.float32)
+    wg = rng.normal(0, 0.3, (E, F, H)).astype(np.float32)
+    wu = rng.normal(0, 0.3, (E, F, H)).astype(np.float32)
+    wd = rng.normal(0, 0.3, (E, H, F)).astype(np.float32)
+    dy = rng.normal(0, 1, (R, H))
+    return offsets, x, wg, wu, wd, dy
+
+
+def test_experts_backward_matches_library_autograd():
+    """The same layer written with torch fp64 ops, differentiated by autograd."""
+    offsets, x, wg, wu, wd, dy = _ffn_case(20, 3, 12, 9, [5, 0, 7])
+    dx, dwg, dwu, dwd = oracle.experts_backward(x, offsets, wg, wu, wd, dy)
+    tx, twg, twu, twd = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (x, wg, wu, wd))
+    ys = []
+    for e in range(3):
+        xe = tx[offsets[e]:offsets[e + 1]]
+        ys.append((torch.nn.functional.silu(xe @ twg[e].T) * (xe @ twu[e].T)) @ twd[e].T)
+    (torch.cat(ys) * torch.tensor(dy)).sum().backward()
+    np.testing.assert_allclose(dx, tx.grad.numpy(), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(dwg, twg.grad.numpy(), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(dwu, twu.grad.numpy(), rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(dwd, twd.grad.numpy(), rtol=1e-11, atol=1e-13)
+    assert (dwg[1] == 0).all() and (dwu[1] == 0).all() and (dwd[1] == 0).all()   # the expert without rows
+
+
+def test_experts_backward_is_the_directional_derivative_of_the_forward_oracle():
+    """Central differences of oracle.experts itself along random directions (all inputs at once)."""
+    offsets, x, wg, wu, wd, dy = _ffn_case(21, 2, 8, 6, [4, 3])
+    dx, dwg, dwu, dwd = oracle.experts_backward(x, offsets, wg, wu, wd, dy)
+    rng = np.random.default_rng(22)
+    dirs = [rng.normal(size=a.shape).astype(np.float32) for a in (x, wg, wu, wd)]
+    h = np.float32(2.0 ** -9)        # exactly representable steps: the perturbed fp32 inputs are exact
+    plus = oracle.experts(x + h * dirs[0], offsets, wg + h * dirs[1], wu + h * dirs[2], wd + h * dirs[3])
+    minus = oracle.experts(x - h * dirs[0], offsets, wg - h * dirs[1], wu - h * dirs[2], wd - h * dirs[3])
+    # the steps actually taken (fp32 rounding of a +- h d)
+    steps = [((a + h * d).astype(np.float64) - (a - h * d).astype(np.float64)) / 2 for a, d in zip((x, wg, wu, wd), dirs)]
+    numeric = ((plus - minus) * dy).sum() / 2
+    analytic = sum((g * s).sum() for g, s in zip((dx, dwg, dwu, dwd), steps))
+    np.testing.assert_allclose(numeric, analytic, rtol=2e-5)
