@@ -196,6 +196,42 @@ moe_status_t moe_permute_backward(const void* dx_perm, const int32_t* row_of_ass
                                   const void* addend, int T, int H, int K, int R_max,
                                   moe_dtype_t dt, void* dx, moe_stream_t stream);
 
+/*
+ * Backward of a3, the grouped SwiGLU expert FFN (bf16 only; Section 3.3: the
+ * backward workflow mirrors the forward; f_e of Eq. 1 by the chain rule).  With
+ * g = x_perm W_gate^T, u = x_perm W_up^T, s = 1/(1+e^-g), h = g s u, for every
+ * expert over its rows and dy_perm given:
+ *
+ *   dw_down[e] = dy_perm^T h               dh = dy_perm W_down[e]
+ *   du = dh g s      dg = dh u s (1 + g (1 - s))
+ *   dw_gate[e] = dg^T x_perm    dw_up[e] = du^T x_perm
+ *   dx_perm = dg W_gate[e] + du W_up[e]
+ *
+ * g and u are recomputed from x_perm (bf16, like every intermediate: g, u, dh,
+ * dg, du are rounded to bf16 once each; accumulation is fp32); h is the
+ * forward's.  The GEMM kernels multiply operands that are contiguous along the
+ * contraction index, so the weights are needed transposed:
+ * moe_expert_weights_transpose writes wgu_t [E,H,2F] = (W_gate[e]^T | W_up[e]^T)
+ * and wd_t [E,F,H] = W_down[e]^T; they stay valid until the weights change (all
+ * micro-batches of a step).  Activations are re-laid inside the workspace.
+ *
+ * x_perm, dy_perm, dx_perm [R_max,H]; h [R_max,F]; dw_gate, dw_up [E,F,H],
+ * dw_down [E,H,F] (bf16; experts without rows get zeros); rows in [R, R_max) of
+ * dx_perm are not touched.  H and F multiples of 128, E <= 256; otherwise
+ * MOE_ERR_UNSUPPORTED.  workspace: moe_expert_backward_workspace_bytes.
+ */
+size_t moe_expert_backward_workspace_bytes(int R_max, int H, int F, int E);
+moe_status_t moe_expert_weights_transpose(const void* w_gate, const void* w_up, const void* w_down,
+                                          int H, int F, int E, void* wgu_t, void* wd_t,
+                                          moe_stream_t stream);
+moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h, const void* dy_perm,
+                                              const int32_t* expert_offsets, int R_max, int H, int F,
+                                              int E, const void* w_gate, const void* w_up,
+                                              const void* wgu_t, const void* wd_t, void* dx_perm,
+                                              void* dw_gate, void* dw_up, void* dw_down,
+                                              void* workspace, size_t workspace_bytes,
+                                              moe_stream_t stream);
+
 /* Bytes of workspace moe_layer_forward needs.  Fs = FFN size of the shared
  * expert (0 = none).  Host only. */
 size_t moe_layer_workspace_bytes(int T, int H, int E, int K, int F, int Fs, int capacity,

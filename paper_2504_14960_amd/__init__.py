@@ -9,13 +9,16 @@ from .binding import (  # noqa: F401
     MOE_F32,
     MoeError,
     capacity_from_factor,
+    expert_backward_workspace_bytes,
     expert_down,
     expert_down_fp8,
     expert_gate_up,
     expert_gate_up_fp8,
+    expert_weights_transpose,
     fp8_delayed_scale,
     fp8_quantize,
     grouped_gemm_swiglu,
+    grouped_gemm_swiglu_backward,
     grouped_gemm_swiglu_fp8,
     layer_forward,
     layer_workspace_bytes,

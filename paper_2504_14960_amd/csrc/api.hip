@@ -272,6 +272,112 @@ moe_status_t moe_permute_backward(const void* dx_perm, const int32_t* row_of_ass
     return check_launch(fn);
 }
 
+struct BackwardLayout {
+    size_t g, u, dh, dgdu, dy_t, h_t, dgdu_t, x_t, total;
+    int rp_max;
+};
+
+static BackwardLayout backward_layout(int R_max, int H, int F, int E) {
+    BackwardLayout L;
+    // bound on the padded column axis of the transposed activations: every non-empty expert's
+    // segment is at most 127 columns longer than its row count
+    const long long nonempty = E < R_max ? E : R_max;
+    L.rp_max = (int)(((long long)R_max + 127 * nonempty + 63) / 64 * 64);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { const size_t at = o; o += up256(bytes); return at; };
+    const size_t rf = (size_t)R_max * F * 2;
+    L.g = take(rf);
+    L.u = take(rf);
+    L.dh = take(rf);
+    L.dgdu = take(2 * rf);
+    L.dy_t = take((size_t)H * L.rp_max * 2);
+    L.h_t = take((size_t)F * L.rp_max * 2);
+    L.dgdu_t = take((size_t)2 * F * L.rp_max * 2);
+    L.x_t = take((size_t)H * L.rp_max * 2);
+    L.total = o;
+    return L;
+}
+
+static bool backward_supported(int H, int F) { return H % 128 == 0 && F % 128 == 0 && H >= 128 && F >= 128; }
+
+size_t moe_expert_backward_workspace_bytes(int R_max, int H, int F, int E) {
+    if (R_max < 0 || H <= 0 || F <= 0 || E <= 0) return 0;
+    return backward_layout(R_max, H, F, E).total;
+}
+
+moe_status_t moe_expert_weights_transpose(const void* w_gate, const void* w_up, const void* w_down,
+                                          int H, int F, int E, void* wgu_t, void* wd_t,
+                                          moe_stream_t stream) {
+    static const char* fn = "moe_expert_weights_transpose";
+    if (H <= 0 || F <= 0 || E <= 0) return fail(MOE_ERR_INVALID_ARG, "%s: need H, F, E > 0", fn);
+    if (!backward_supported(H, F)) return fail(MOE_ERR_UNSUPPORTED, "%s: H=%d and F=%d must be multiples of 128", fn, H, F);
+    REQUIRE_PTR(fn, w_gate);
+    REQUIRE_PTR(fn, w_up);
+    REQUIRE_PTR(fn, w_down);
+    REQUIRE_PTR(fn, wgu_t);
+    REQUIRE_PTR(fn, wd_t);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    launch_transpose_batched(w_gate, E, F, H, wgu_t, (size_t)2 * F, 0, s);   // [E,F,H] -> [E,H,0:F]
+    launch_transpose_batched(w_up, E, F, H, wgu_t, (size_t)2 * F, F, s);     //            [E,H,F:2F]
+    launch_transpose_batched(w_down, E, H, F, wd_t, (size_t)H, 0, s);        // [E,H,F] -> [E,F,H]
+    return check_launch(fn);
+}
+
+moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h, const void* dy_perm,
+                                              const int32_t* expert_offsets, int R_max, int H, int F,
+                                              int E, const void* w_gate, const void* w_up,
+                                              const void* wgu_t, const void* wd_t, void* dx_perm,
+                                              void* dw_gate, void* dw_up, void* dw_down,
+                                              void* workspace, size_t workspace_bytes,
+                                              moe_stream_t stream) {
+    static const char* fn = "moe_grouped_gemm_swiglu_backward";
+    if (R_max < 0 || H <= 0 || F <= 0 || E <= 0) return fail(MOE_ERR_INVALID_ARG, "%s: need R_max >= 0 and H, F, E > 0", fn);
+    if (E > kMaxExperts) return fail(MOE_ERR_UNSUPPORTED, "%s: E=%d exceeds the limit %d", fn, E, kMaxExperts);
+    if (!backward_supported(H, F)) return fail(MOE_ERR_UNSUPPORTED, "%s: H=%d and F=%d must be multiples of 128", fn, H, F);
+    REQUIRE_PTR(fn, expert_offsets);
+    REQUIRE_PTR(fn, dw_gate);
+    REQUIRE_PTR(fn, dw_up);
+    REQUIRE_PTR(fn, dw_down);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const BackwardLayout L = backward_layout(R_max, H, F, E);
+    if (R_max > 0) {
+        REQUIRE_PTR(fn, x_perm);
+        REQUIRE_PTR(fn, h);
+        REQUIRE_PTR(fn, dy_perm);
+        REQUIRE_PTR(fn, w_gate);
+        REQUIRE_PTR(fn, w_up);
+        REQUIRE_PTR(fn, wgu_t);
+        REQUIRE_PTR(fn, wd_t);
+        REQUIRE_PTR(fn, dx_perm);
+        if (workspace == nullptr || workspace_bytes < L.total)
+            return fail(MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, L.total,
+                        workspace ? workspace_bytes : (size_t)0);
+        REQUIRE_PTR(fn, workspace);
+    }
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    if (R_max > 0) {
+        // recompute g and u; dh; the SwiGLU's derivative; the input gradient
+        bool ok = launch_grouped_nt(x_perm, expert_offsets, R_max, E, F, H, w_gate, ws + L.g, s);
+        ok = ok && launch_grouped_nt(x_perm, expert_offsets, R_max, E, F, H, w_up, ws + L.u, s);
+        ok = ok && launch_grouped_nt(dy_perm, expert_offsets, R_max, E, F, H, wd_t, ws + L.dh, s);
+        if (!ok) return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
+        launch_swiglu_backward(ws + L.dh, ws + L.g, ws + L.u, expert_offsets + E, R_max, F, ws + L.dgdu, s);
+        if (!launch_grouped_nt(ws + L.dgdu, expert_offsets, R_max, E, H, 2 * F, wgu_t, dx_perm, s))
+            return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
+        // operands of the weight gradients, transposed with every expert's rows as a zero-padded column segment
+        launch_ragged_transpose(dy_perm, expert_offsets, E, H, L.rp_max, ws + L.dy_t, s);
+        launch_ragged_transpose(h, expert_offsets, E, F, L.rp_max, ws + L.h_t, s);
+        launch_ragged_transpose(ws + L.dgdu, expert_offsets, E, 2 * F, L.rp_max, ws + L.dgdu_t, s);
+        launch_ragged_transpose(x_perm, expert_offsets, E, H, L.rp_max, ws + L.x_t, s);
+    }
+    // with R_max == 0 every segment is empty and the three launches below write zeros without reading
+    const int ld = R_max > 0 ? L.rp_max : 64;
+    launch_wgrad_gemm(ws + L.dy_t, ws + L.h_t, expert_offsets, E, H, F, ld, dw_down, s);
+    launch_wgrad_gemm(ws + L.dgdu_t, ws + L.x_t, expert_offsets, E, F, H, ld, dw_gate, s);
+    launch_wgrad_gemm(ws + L.dgdu_t + (size_t)F * ld * 2, ws + L.x_t, expert_offsets, E, F, H, ld, dw_up, s);
+    return check_launch(fn);
+}
+
 size_t moe_layer_workspace_bytes(int T, int H, int E, int K, int F, int Fs, int capacity,
                                  moe_dtype_t dt) {
     if (T < 0 || H <= 0 || E <= 0 || K <= 0 || F <= 0 || Fs < 0) return 0;

@@ -71,6 +71,22 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
 
 void launch_fill_i32(int32_t* p, int n, int32_t v0, int32_t step, hipStream_t s);
 
+// ---- pieces of the expert FFN's backward (bf16) ----
+// C [rows, N] = A [rows, K] . B[e]^T, B [E, N, K], rows grouped by expert; false if the shape is not covered
+bool launch_grouped_nt(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B,
+                       void* C, hipStream_t s);
+// dst[b][c][col0 + r] = src[b][r][c], dst rows ld_out elements long
+void launch_transpose_batched(const void* src, int B, int R, int C, void* dst, size_t ld_out, int col0, hipStream_t s);
+// dst [C, rp_max]: rows of expert e of src [rows, C] become the columns of its zero-padded segment
+void launch_ragged_transpose(const void* src, const int32_t* offsets, int E, int C, int rp_max, void* dst,
+                             hipStream_t s);
+// out [rows, 2F] = dg | du from dh, g, u [rows, F]; rows = *n_rows (device)
+void launch_swiglu_backward(const void* dh, const void* g, const void* u, const int32_t* n_rows, int r_max, int F,
+                            void* out, hipStream_t s);
+// dw [E, M, N] = per expert a_t[:, seg_e] . b_t[:, seg_e]^T over the expert's padded column segment
+void launch_wgrad_gemm(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
+                       void* dw, hipStream_t s);
+
 // FP8 (E4M3) path of the expert FFN: per-tensor quantisation with amax, and the
 // two grouped GEMMs on quantised operands (phase bits as above)
 void launch_fp8_quantize(const void* src, moe_dtype_t dt, size_t n, float scale, void* dst, float* amax,

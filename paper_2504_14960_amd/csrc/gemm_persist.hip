@@ -433,6 +433,15 @@ void run_persist_pair(const void* x_perm, const int32_t* offsets, int r_max, int
 
 void set_persist_workgroups(int n) { g_persist_workgroups = n; }
 
+// C [rows, N] = A [rows, K] . B[e]^T with B [E, N, K], rows grouped by expert (bf16): the
+// down-projection form of the persistent kernel, for any operands of that shape
+bool launch_grouped_nt(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B,
+                       void* C, hipStream_t s) {
+    if (K < 128 || K % 64 || N % 8) return false;
+    launch_persist<256, 256, 2, 4, false>(A, offsets, r_max, E, N, K, B, nullptr, C, s);
+    return true;
+}
+
 bool launch_persist_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                         const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm,
                         int variant, int phase, hipStream_t s) {

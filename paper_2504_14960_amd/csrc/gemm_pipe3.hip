@@ -24,10 +24,19 @@ namespace moe {
 
 namespace {
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+// GROUPK = false: the forward's grouped GEMM, rows grouped by expert (ragged M),
+// one contraction length K for all.
+// GROUPK = true: the weight-gradient form.  C [E, M, N] = for every expert e,
+// A[:, seg_e] . B[:, seg_e]^T, where A [M, ld] and B [N, ld] hold transposed
+// activations whose columns are grouped by expert: segment e starts at the sum of
+// the padded lengths of the experts before it and is padded with zeros to
+// padded(n_e) = max(128, n_e rounded up to 64) columns (0 for an empty expert).
+// One workgroup per (expert, M-tile, N-tile); its contraction runs over the
+// expert's segment only; `K` carries ld, `ntn` the N-tile count, `M` the rows.
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, bool GROUPK = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
-    const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, int ntn) {
+    const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, int ntn, int M) {
     constexpr int BK = 64;
     constexpr int NT = WGM * WGN * 64;
     constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -70,8 +79,31 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     // written before the prologue's barrier
     int* sched = reinterpret_cast<int*>(smem + (TRI_B ? A_BYTES : B_REGION + B_BYTES));  // second early slot
 
-    const Tile tile = find_tile<BM>(offsets, E, ntn, sched);
-    if (!tile.valid) return;
+    Tile tile;
+    int seg_off = 0, seg_len = 0;   // GROUPK: the expert's column segment
+    if constexpr (GROUPK) {
+        static_assert(!SWIGLU, "the weight-gradient form has one B operand");
+        (void)sched;
+        const int mt = (M + BM - 1) / BM;
+        const int per_e = mt * ntn;
+        const int e = blockIdx.x / per_e, rem = blockIdx.x - e * per_e;
+        const int nt = rem / mt, m = rem - nt * mt;   // M-tiles of one weight panel are neighbours
+        tile.valid = e < E;
+        if (!tile.valid) return;
+        for (int q = 0; q <= e; ++q) {   // wave-uniform, E <= 256 short iterations
+            const int n_q = offsets[q + 1] - offsets[q];
+            const int pn = n_q <= 0 ? 0 : max(128, (n_q + 63) & ~63);
+            if (q < e) seg_off += pn; else seg_len = pn;
+        }
+        tile.expert = e;
+        tile.row0 = e * M + m * BM;          // row of C
+        tile.rows = min(BM, M - m * BM);
+        tile.row_end = (e + 1) * M;
+        tile.ntile = nt;
+    } else {
+        tile = find_tile<BM>(offsets, E, ntn, sched);
+        if (!tile.valid) return;
+    }
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -79,8 +111,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     const int n0 = tile.ntile * OUTN;
 
     const int frow = tid / CPR, fchunk = tid % CPR;
-    const uint8_t* a_base = reinterpret_cast<const uint8_t*>(A + (size_t)tile.row0 * K);
-    const size_t b_row0 = ((size_t)tile.expert * N + n0) * K;
+    const uint8_t* a_base = GROUPK
+        ? reinterpret_cast<const uint8_t*>(A + (size_t)(tile.row0 - tile.expert * M) * K + seg_off)
+        : reinterpret_cast<const uint8_t*>(A + (size_t)tile.row0 * K);
+    const size_t b_row0 = GROUPK ? (size_t)n0 * K + seg_off : ((size_t)tile.expert * N + n0) * K;
     const uint8_t* b_base0 = reinterpret_cast<const uint8_t*>(B0 + b_row0);
     const uint8_t* b_base1 = SWIGLU ? reinterpret_cast<const uint8_t*>(B1 + b_row0) : b_base0;
     uint32_t a_goff[PA], b_goff[PB];
@@ -192,7 +226,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    const int KT = K / BK;
+    const int KT = GROUPK ? seg_len / BK : K / BK;
+    if (GROUPK && KT == 0) {
+        // an expert without rows: its weight gradient is zero
+        store_tile<FM, FN, WM, WN, BN, SWIGLU>(acc, tile, C, N, n0, wm, wn, lane);
+        return;
+    }
     auto kb = [&](int kt) { return min(kt, KT - 1) * (BK * 2); };  // past the end: the last tile again, never used
     uint8_t* const e_region = smem + (TRI_B ? 0 : B_REGION);   // early operand: 2 slots
     uint8_t* const l_region = smem + (TRI_B ? B_REGION : 0);   // late operand: 3 slots
@@ -253,7 +292,7 @@ void launch_pipe3(const void* A, const int32_t* offsets, int r_max, int E, int N
     constexpr int OUTN = SWIGLU ? BN / 2 : BN;
     constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
     const int ntn = (N + OUTN - 1) / OUTN;
-    auto kern = gemm_bf16_pipe3_kernel<BM, BN, WGM, WGN, SWIGLU>;
+    auto kern = gemm_bf16_pipe3_kernel<BM, BN, WGM, WGN, SWIGLU, false>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -263,7 +302,25 @@ void launch_pipe3(const void* A, const int32_t* offsets, int r_max, int E, int N
     const int grid = grid_for(r_max, E, BM, ntn);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A),
                        offsets, E, N, K, static_cast<const bf16_t*>(B0),
-                       static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C), ntn);
+                       static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C), ntn, 0);
+}
+
+// weight-gradient form: C [E, M, N] from A [M, ld] and B [N, ld] (see the kernel)
+template <int BM, int BN, int WGM, int WGN>
+void launch_pipe3_groupk(const void* A, const void* B, const int32_t* offsets, int E, int M, int N, int ld,
+                         void* C, hipStream_t s) {
+    constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
+    const int ntn = (N + BN - 1) / BN, mt = (M + BM - 1) / BM;
+    auto kern = gemm_bf16_pipe3_kernel<BM, BN, WGM, WGN, false, true>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(E * mt * ntn), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A),
+                       offsets, E, N, ld, static_cast<const bf16_t*>(B), static_cast<const bf16_t*>(B),
+                       static_cast<bf16_t*>(C), ntn, M);
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -275,6 +332,11 @@ void run_pipe3_pair(const void* x_perm, const int32_t* offsets, int r_max, int H
 }
 
 }  // namespace
+
+void launch_wgrad_gemm(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
+                       void* dw, hipStream_t s) {
+    launch_pipe3_groupk<256, 256, 2, 4>(a_t, b_t, offsets, E, M, N, ld, dw, s);
+}
 
 bool launch_pipe3_ffn(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                       const void* w_gate, const void* w_up, const void* w_down, void* h,

@@ -62,3 +62,82 @@ def test_permute_backward_against_oracle(T, H, E, K, capacity, bf16, with_addend
     if not with_addend:
         none_kept = (perm.row_of_assign.reshape(T, K) < 0).all(axis=1)
         assert (values(to_host(dx))[none_kept] == 0).all()
+
+
+def _ffn_backward_case(H, F, E, counts, seed):
+    from moe_inputs import get_config, make_layer_inputs
+    cfg = get_config("mixtral8x7b").scaled(T=8, H=H, E=E, K=1, F=F, seed=seed)
+    inp = make_layer_inputs(cfg, ["w_gate", "w_up", "w_down"])
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R = int(offsets[-1])
+    x = make_tokens(seed + 1, max(R, 1), H, bf16=True)
+    dy = make_tokens(seed + 2, max(R, 1), H, bf16=True)
+    want = oracle.experts_backward(x, offsets, inp["w_gate"], inp["w_up"], inp["w_down"], values(dy)[:R])
+    return inp, offsets, R, x, dy, want
+
+
+def _run_ffn_backward(inp, offsets, R, x, dy, r_pad=0):
+    import torch
+    import paper_2504_14960_amd as moe
+    E, F, H = inp["w_gate"].shape
+    r_max = R + r_pad
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    dx_in = torch.zeros((r_max, H), **bf)
+    dy_in = torch.zeros((r_max, H), **bf)
+    dx_in[:R] = to_dev(x)[:R]
+    dy_in[:R] = to_dev(dy)[:R]
+    wg, wu, wd = to_dev(inp["w_gate"]), to_dev(inp["w_up"]), to_dev(inp["w_down"])
+    off = to_dev(offsets)
+    h = torch.zeros((r_max, F), **bf)
+    y = torch.zeros((r_max, H), **bf)
+    moe.grouped_gemm_swiglu(dx_in, off, wg, wu, wd, h, y)          # the forward leaves h behind
+    wgu_t = torch.empty((E, H, 2 * F), **bf)
+    wd_t = torch.empty((E, F, H), **bf)
+    moe.expert_weights_transpose(wg, wu, wd, wgu_t, wd_t)
+    dxp = torch.zeros((r_max, H), **bf)
+    dwg, dwu, dwd = torch.full((E, F, H), 7.0, **bf), torch.full((E, F, H), 7.0, **bf), torch.full((E, H, F), 7.0, **bf)
+    ws = torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda")
+    moe.grouped_gemm_swiglu_backward(dx_in, h, dy_in, off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
+    torch.cuda.synchronize()
+    # the transposes are plain copies: check them bit for bit against the host
+    np.testing.assert_array_equal(to_host(wd_t), np.ascontiguousarray(inp["w_down"].transpose(0, 2, 1)))
+    np.testing.assert_array_equal(to_host(wgu_t)[:, :, :F], np.ascontiguousarray(inp["w_gate"].transpose(0, 2, 1)))
+    np.testing.assert_array_equal(to_host(wgu_t)[:, :, F:], np.ascontiguousarray(inp["w_up"].transpose(0, 2, 1)))
+    return to_host(dxp), to_host(dwg), to_host(dwu), to_host(dwd)
+
+
+def _assert_grad_close(got, ref, what):
+    """Gradients pass through five bf16 roundings (g, u, dh, dg|du, result) instead of the forward's three:
+    max |d| <= 3e-2 max|ref|, relative L2 <= 1e-2."""
+    g, r = values(got), np.asarray(ref, dtype=np.float64)
+    assert np.isfinite(g).all(), what
+    d = g - r
+    assert np.abs(d).max() <= 3e-2 * np.abs(r).max() + 1e-30, f"{what}: max|d|={np.abs(d).max():.3e} vs {np.abs(r).max():.3e}"
+    nr = np.linalg.norm(r)
+    assert nr == 0 or np.linalg.norm(d) / nr <= 1e-2, f"{what}: rel-L2={np.linalg.norm(d) / nr:.3e}"
+
+
+@pytest.mark.parametrize("H,F,E,counts", [
+    (256, 384, 6, [700, 0, 1, 300, 513, 86]),      # ragged tiles, an empty expert, a 1-row expert
+    (128, 128, 3, [64, 130, 5]),                   # smallest supported sizes
+    (384, 256, 64, None),                          # many small experts
+])
+def test_expert_ffn_backward_against_oracle(H, F, E, counts):
+    if counts is None:
+        counts = np.random.default_rng(12).integers(0, 90, size=E).tolist()
+    inp, offsets, R, x, dy, want = _ffn_backward_case(H, F, E, counts, 8000 + H + E)
+    dx, dwg, dwu, dwd = _run_ffn_backward(inp, offsets, R, x, dy, r_pad=9)
+    assert (values(dx)[R:] == 0).all()                     # rows past the kept ones untouched
+    _assert_grad_close(dx[:R], want[0], "dx_perm")
+    _assert_grad_close(dwg, want[1], "dw_gate")
+    _assert_grad_close(dwu, want[2], "dw_up")
+    _assert_grad_close(dwd, want[3], "dw_down")
+    for e, n in enumerate(counts):
+        if n == 0:                                         # experts without rows: exact zeros
+            assert (values(dwg)[e] == 0).all() and (values(dwu)[e] == 0).all() and (values(dwd)[e] == 0).all()
+
+
+def test_expert_ffn_backward_with_no_rows_gives_zero_weight_gradients():
+    inp, offsets, R, x, dy, want = _ffn_backward_case(128, 128, 4, [0, 0, 0, 0], 8100)
+    dx, dwg, dwu, dwd = _run_ffn_backward(inp, offsets, R, x, dy, r_pad=16)
+    assert (values(dx) == 0).all() and (values(dwg) == 0).all() and (values(dwu) == 0).all() and (values(dwd) == 0).all()
