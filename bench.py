@@ -44,6 +44,9 @@ def parse_args():
                     help="fp8: expert FFN on E4M3 operands with delayed per-tensor scaling (weights quantised "
                          "beforehand and resident, activations quantised inside the timed step); a separate "
                          "experiment, the headline metric is the bf16 run")
+    ap.add_argument("--ffn-backward", action="store_true",
+                    help="also time the backward of the grouped expert FFN (and the one-off weight transposes it "
+                         "needs) on the same routing; reported in a separate object, not part of the step")
     ap.add_argument("--dispatch-backward", action="store_true",
                     help="also time the backward of the dispatcher's two data movements (combine backward, permute "
                          "backward) on the same routing; reported in a separate object, not part of the step")
@@ -303,6 +306,41 @@ def main():
         "context": "the paper reports 49.3 % (Mixtral 8x22B) and 39.0 % (Qwen2-57B-A14B) MFU for whole training "
                    "steps on H100 clusters: other hardware, other scope, shown for orientation only",
     }
+    if args.ffn_backward and not fp8 and bf16:
+        s0 = sets[0]
+        bfk = dict(dtype=torch.bfloat16, device="cuda")
+        wgu_t = torch.empty((E, H, 2 * F), **bfk)
+        wd_t = torch.empty((E, F, H), **bfk)
+        dwg, dwu, dwd = torch.empty((E, F, H), **bfk), torch.empty((E, F, H), **bfk), torch.empty((E, H, F), **bfk)
+        dxp = torch.empty((r_max, H), **bfk)
+        bws = torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda")
+
+        def timed(fn, n, w):
+            for _ in range(w):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        n_b, w_b = max(3, args.steps // 4), 2
+        t_tr = timed(lambda: moe.expert_weights_transpose(w["w_gate"], w["w_up"], w["w_down"], wgu_t, wd_t), n_b, w_b)
+        # y_perm stands in for the incoming gradient dy_perm (same shape and value range)
+        t_bw = timed(lambda: moe.grouped_gemm_swiglu_backward(s0["x_perm"], s0["h"], s0["y_perm"], s0["offsets"],
+                                                              w["w_gate"], w["w_up"], wgu_t, wd_t, dxp, dwg, dwu, dwd,
+                                                              bws), n_b, w_b)
+        useful = 12.0 * R * H * F            # dh, dx (2 products), three weight gradients
+        out["ffn_backward"] = {
+            "ms": round(t_bw, 4), "useful_tflops": round(useful / (t_bw * 1e-3) / 1e12, 1),
+            "frac_of_bf16_peak": round(useful / (t_bw * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "executed_flop_over_useful": round(16.0 / 12.0, 3),   # g and u are recomputed: 4 R H F more
+            "weights_transpose_ms": round(t_tr, 4),
+            "weights_transpose_gbs": round(2 * 3 * E * H * F * es / (t_tr * 1e-3) / 1e9, 1),
+            "workspace_gb": round(bws.numel() / 1e9, 2)}
     if args.dispatch_backward and not fp8:
         # dy plays the gradient of the layer output; the forward's y_perm, maps and gates are reused
         res = {}

@@ -225,3 +225,77 @@ def test_full_size_fp8_expert_ffn(name):
     y_ref = oracle.combine(ref.y, roa_s.reshape(-1), want_gate[tokens], None)
     dev_tok = torch.from_numpy(tokens.astype(np.int64)).cuda()
     assert_close(to_host(y[dev_tok]), y_ref, True, f"fp8 y rows ({name})")
+
+
+@pytest.mark.parametrize("name", ["mixtral8x22b", "mixtral8x22b_g8t8"])
+def test_full_size_ffn_backward(name):
+    """The expert FFN's backward at full size, launched as bench.py --ffn-backward does.  dx_perm on sampled rows
+    (a row's input gradient depends on that row only); weight gradients on sampled features of sampled experts: the
+    gradients of gate/up row f and of down column f depend on the other features only through nothing at all, so a
+    layer cut down to a few features, with all rows of the expert, gives exactly those entries."""
+    import torch
+    import paper_2504_14960_amd as moe
+    cfg = get_config(name)
+    T, H, E, K, F = cfg.T, cfg.H, cfg.E, cfg.K, cfg.F
+    inp = make_layer_inputs(cfg)
+    capacity = capacity_rows(cfg)
+    t = inp.tensors
+    l64 = oracle.router_logits(t["x"], t["w_router"], inp.bias)
+    idx, _ = oracle.topk_gates(l64.astype(np.float32), K, cfg.renormalize)
+    perm = oracle.permute(None, idx, E, capacity)
+    R = perm.R
+    r_max = R
+    token_of_row = perm.assign_of_row[:R] // K
+    x_perm = np.ascontiguousarray(t["x"][token_of_row])
+    from moe_inputs import make_tokens
+    dy = make_tokens(cfg.seed + 77, R, H, bf16=True)
+
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    d_x, d_dy, off = to_dev(x_perm), to_dev(dy), to_dev(perm.offsets)
+    wg, wu, wd = to_dev(t["w_gate"]), to_dev(t["w_up"]), to_dev(t["w_down"])
+    h = torch.empty((r_max, F), **bf)
+    y = torch.empty((r_max, H), **bf)
+    moe.grouped_gemm_swiglu(d_x, off, wg, wu, wd, h, y)
+    del y
+    wgu_t, wd_t = torch.empty((E, H, 2 * F), **bf), torch.empty((E, F, H), **bf)
+    moe.expert_weights_transpose(wg, wu, wd, wgu_t, wd_t)
+    dxp = torch.empty((r_max, H), **bf)
+    dwg, dwu, dwd = torch.empty((E, F, H), **bf), torch.empty((E, F, H), **bf), torch.empty((E, H, F), **bf)
+    ws = torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda")
+    moe.grouped_gemm_swiglu_backward(d_x, h, d_dy, off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
+    torch.cuda.synchronize()
+
+    def close(got, ref, what):     # the gradient bar of tests/test_gpu_backward.py
+        g, r = values(got), np.asarray(ref, dtype=np.float64)
+        d = g - r
+        assert np.isfinite(g).all(), what
+        assert np.abs(d).max() <= 3e-2 * np.abs(r).max() + 1e-30, f"{what}: max|d| {np.abs(d).max():.3e}"
+        assert np.linalg.norm(d) / np.linalg.norm(r) <= 1e-2, f"{what}: rel-L2 {np.linalg.norm(d) / np.linalg.norm(r):.3e}"
+
+    rng = np.random.default_rng(cfg.seed + 3)
+    # ---- dx_perm on sampled rows, with the full weights ----
+    rows = np.sort(rng.choice(R, size=16, replace=False))
+    expert_of_row = np.searchsorted(perm.offsets, rows, side="right") - 1
+    sub_off = np.concatenate([[0], np.cumsum(np.bincount(expert_of_row, minlength=E))]).astype(np.int32)
+    dx_ref = oracle.experts_backward(np.ascontiguousarray(x_perm[rows]), sub_off, t["w_gate"], t["w_up"], t["w_down"],
+                                     values(dy[rows]))[0]
+    dev_rows = torch.from_numpy(rows.astype(np.int64)).cuda()
+    close(to_host(dxp[dev_rows]), dx_ref, f"dx_perm rows ({name})")
+
+    # ---- weight gradients of sampled features of sampled experts, over all rows of the expert ----
+    nonempty = np.nonzero(perm.counts > 0)[0]
+    for e in rng.choice(nonempty, size=min(2, nonempty.size), replace=False):
+        lo, hi = int(perm.offsets[e]), int(perm.offsets[e + 1])
+        feats = np.sort(rng.choice(F, size=4, replace=False))
+        mini_g = np.ascontiguousarray(t["w_gate"][e][feats])[None]          # [1, 4, H]
+        mini_u = np.ascontiguousarray(t["w_up"][e][feats])[None]
+        mini_d = np.ascontiguousarray(t["w_down"][e][:, feats])[None]       # [1, H, 4]
+        one = np.array([0, hi - lo], dtype=np.int32)
+        _, rg, ru, rd = oracle.experts_backward(np.ascontiguousarray(x_perm[lo:hi]), one, mini_g, mini_u, mini_d,
+                                                values(dy[lo:hi]))
+        f_dev = torch.from_numpy(feats.astype(np.int64)).cuda()
+        close(to_host(dwg[e][f_dev]), rg[0], f"dw_gate expert {e} ({name})")
+        close(to_host(dwu[e][f_dev]), ru[0], f"dw_up expert {e} ({name})")
+        close(to_host(dwd[e][:, f_dev].contiguous()), rd[0], f"dw_down expert {e} ({name})")
+    for e in np.nonzero(perm.counts == 0)[0]:
+        assert (values(to_host(dwd[int(e)])) == 0).all()
