@@ -170,6 +170,25 @@ def combine(y_perm: np.ndarray, row_of_assign: np.ndarray, gate: np.ndarray,
     return y
 
 
+def router_backward(x: np.ndarray, w_router: np.ndarray, logits32: np.ndarray, idx: np.ndarray, dgate: np.ndarray,
+                    renormalize: bool):
+    """Backward of the router: returns (dlogits [T,E], dx [T,H], dw_router [E,H], dbias [E]) in double."""
+    T, H = x.shape
+    E = w_router.shape[0]
+    logits32 = np.ascontiguousarray(logits32, dtype=np.float32)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    dgate = np.ascontiguousarray(dgate, dtype=np.float64)
+    K = idx.shape[1]
+    assert logits32.shape == (T, E) and dgate.shape == (T, K) and _dt(x) == _dt(w_router)
+    dl = np.zeros((T, E), dtype=np.float64)
+    dx = np.zeros((T, H), dtype=np.float64)
+    dw = np.zeros((E, H), dtype=np.float64)
+    db = np.zeros(E, dtype=np.float64)
+    lib().oracle_router_backward(_p(np.ascontiguousarray(x)), _p(np.ascontiguousarray(w_router)), _p(logits32), _p(idx),
+                                 _p(dgate), T, H, E, K, int(bool(renormalize)), _dt(x), _p(dl), _p(dx), _p(dw), _p(db))
+    return dl, dx, dw, db
+
+
 def experts_backward(x_perm: np.ndarray, offsets: np.ndarray, w_gate: np.ndarray, w_up: np.ndarray,
                      w_down: np.ndarray, dy: np.ndarray):
     """Backward of experts(): returns (dx [R,H], dw_gate [E,F,H], dw_up [E,F,H], dw_down [E,H,F]) in double."""

@@ -355,6 +355,85 @@ void oracle_combine(const double* y_perm, const int32_t* row_of_assign, const do
         }
 }
 
+/* ---- backward of the router (Eq. 2 + Eq. 3 by the chain rule; Section 3.3: the
+ * backward workflow mirrors the forward one) ----
+ * Forward: l = x W_g^T (+ bias), p = softmax(l), gate_k = p[idx_k], optionally
+ * divided by S = sum_k p[idx_k].  The selection idx is piecewise constant, so
+ * its derivative is zero; given dgate [T,K]:
+ *   without renormalisation  q_k = dgate_k
+ *   with renormalisation     q_k = (dgate_k - sum_j dgate_j gate_j) / S
+ *   dl_e = [e = idx_k] q_k p_e  -  p_e sum_k q_k p[idx_k]          (softmax Jacobian)
+ *   dx[t,:] = sum_e dl[t,e] W_g[e,:]    dW_g[e,:] = sum_t dl[t,e] x[t,:]    dbias[e] = sum_t dl[t,e]
+ * logits are the fp32 logits the forward kept.  An index outside [0,E) has no gradient.
+ * dx, dw, dbias may be NULL. */
+void oracle_router_backward(const void* x, const void* w_router, const float* logits,
+                            const int32_t* idx, const double* dgate, int T, int H, int E, int K,
+                            int renormalize, int dt, double* dlogits, double* dx, double* dw,
+                            double* dbias) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        const float* l = logits + (size_t)t * E;
+        double* p = (double*)malloc(sizeof(double) * (size_t)E);
+        double* q = (double*)malloc(sizeof(double) * (size_t)K);
+        double m = -INFINITY, z = 0.0;
+        for (int e = 0; e < E; ++e)
+            if ((double)l[e] > m) m = (double)l[e];
+        for (int e = 0; e < E; ++e) {
+            p[e] = exp((double)l[e] - m);
+            z += p[e];
+        }
+        for (int e = 0; e < E; ++e) p[e] /= z;
+        double S = 0.0, a = 0.0;
+        for (int k = 0; k < K; ++k) {
+            int e = idx[(size_t)t * K + k];
+            if (e >= 0 && e < E) S += p[e];
+        }
+        for (int k = 0; k < K; ++k) {
+            int e = idx[(size_t)t * K + k];
+            if (e >= 0 && e < E) a += dgate[(size_t)t * K + k] * (p[e] / S);
+        }
+        double sum_qp = 0.0;
+        for (int k = 0; k < K; ++k) {
+            int e = idx[(size_t)t * K + k];
+            q[k] = 0.0;
+            if (e < 0 || e >= E) continue;
+            q[k] = renormalize ? (dgate[(size_t)t * K + k] - a) / S : dgate[(size_t)t * K + k];
+            sum_qp += q[k] * p[e];
+        }
+        for (int e = 0; e < E; ++e) dlogits[(size_t)t * E + e] = -p[e] * sum_qp;
+        for (int k = 0; k < K; ++k) {
+            int e = idx[(size_t)t * K + k];
+            if (e >= 0 && e < E) dlogits[(size_t)t * E + e] += q[k] * p[e];
+        }
+        free(p);
+        free(q);
+    }
+    if (dx) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int t = 0; t < T; ++t)
+            for (int n = 0; n < H; ++n) {
+                double acc = 0.0;
+                for (int e = 0; e < E; ++e) acc += dlogits[(size_t)t * E + e] * ld(w_router, (size_t)e * H + n, dt);
+                dx[(size_t)t * H + n] = acc;
+            }
+    }
+    if (dw) {
+#pragma omp parallel for collapse(2) schedule(static)
+        for (int e = 0; e < E; ++e)
+            for (int n = 0; n < H; ++n) {
+                double acc = 0.0;
+                for (int t = 0; t < T; ++t) acc += dlogits[(size_t)t * E + e] * ld(x, (size_t)t * H + n, dt);
+                dw[(size_t)e * H + n] = acc;
+            }
+    }
+    if (dbias)
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int t = 0; t < T; ++t) acc += dlogits[(size_t)t * E + e];
+            dbias[e] = acc;
+        }
+}
+
 /* ---- backward of the dispatcher's two data movements (Section 3.3: the
  * backward workflow mirrors the forward one) ----
  *

@@ -120,3 +120,52 @@ def test_experts_backward_is_the_directional_derivative_of_the_forward_oracle():
     numeric = ((plus - minus) * dy).sum() / 2
     analytic = sum((g * s).sum() for g, s in zip((dx, dwg, dwu, dwd), steps))
     np.testing.assert_allclose(numeric, analytic, rtol=2e-5)
+
+
+@pytest.mark.parametrize("renorm", [False, True])
+@pytest.mark.parametrize("T,H,E,K", [(9, 6, 8, 2), (5, 4, 5, 5), (7, 3, 16, 1)])
+def test_router_backward_matches_library_autograd(T, H, E, K, renorm):
+    rng = np.random.default_rng(30 + T + E)
+    x = rng.normal(0, 1, (T, H)).astype(np.float32)
+    w = rng.normal(0, 0.5, (E, H)).astype(np.float32)
+    bias = rng.normal(0, 0.5, E).astype(np.float32)
+    logits32 = oracle.router_logits(x, w, bias).astype(np.float32)
+    idx, gate = oracle.topk_gates(logits32, K, renorm)
+    dgate = rng.normal(size=(T, K))
+    dl, dx, dw, db = oracle.router_backward(x, w, logits32, idx, dgate, renorm)
+    # the same gating written with torch fp64 ops on the same fp32 logits, differentiated by autograd
+    tl = torch.tensor(logits32.astype(np.float64), requires_grad=True)
+    p = torch.softmax(tl, dim=1)
+    g = torch.gather(p, 1, torch.tensor(idx.astype(np.int64)))
+    if renorm:
+        g = g / g.sum(dim=1, keepdim=True)
+    np.testing.assert_allclose(g.detach().numpy(), gate, rtol=1e-12)
+    (g * torch.tensor(dgate)).sum().backward()
+    np.testing.assert_allclose(dl, tl.grad.numpy(), rtol=1e-10, atol=1e-14)
+    # logits = x W^T + bias: the two products and the column sums, with numpy
+    np.testing.assert_allclose(dx, dl @ w.astype(np.float64), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(dw, dl.T @ x.astype(np.float64), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(db, dl.sum(axis=0), rtol=1e-12, atol=1e-15)
+    # softmax is shift invariant: the logit gradients of a token sum to zero
+    assert np.abs(dl.sum(axis=1)).max() < 1e-14
+    if renorm:
+        # renormalised gates sum to one: a constant dgate has no effect
+        dl0 = oracle.router_backward(x, w, logits32, idx, np.full((T, K), 3.7), True)[0]
+        assert np.abs(dl0).max() < 1e-14
+
+
+def test_router_backward_ignores_out_of_range_indices():
+    rng = np.random.default_rng(40)
+    T, H, E, K = 4, 3, 6, 3
+    x = rng.normal(size=(T, H)).astype(np.float32)
+    w = rng.normal(size=(E, H)).astype(np.float32)
+    logits32 = rng.normal(size=(T, E)).astype(np.float32)
+    idx = np.array([[0, 7, 2], [1, -1, 3], [5, 4, 0], [2, 3, 99]], dtype=np.int32)
+    dgate = rng.normal(size=(T, K))
+    dl = oracle.router_backward(x, w, logits32, idx, dgate, False)[0]
+    idx_ok = idx.copy()
+    dg_ok = dgate.copy()
+    bad = (idx < 0) | (idx >= E)
+    idx_ok[bad] = 0
+    dg_ok[bad] = 0.0          # an out-of-range slot behaves like a slot whose gate gradient is zero
+    np.testing.assert_allclose(dl, oracle.router_backward(x, w, logits32, idx_ok, dg_ok, False)[0], rtol=1e-13, atol=1e-16)
