@@ -197,6 +197,31 @@ moe_status_t moe_permute_backward(const void* dx_perm, const int32_t* row_of_ass
                                   moe_dtype_t dt, void* dx, moe_stream_t stream);
 
 /*
+ * Backward of a1, the router (Eq. 2 + Eq. 3 by the chain rule).  The selection
+ * is piecewise constant and has no gradient.  With p = softmax(logits[t,:]) and
+ * S = sum_k p[idx_k]:
+ *
+ *   q_k = dgate[t,k]                                  (renormalize == 0)
+ *   q_k = (dgate[t,k] - sum_j dgate[t,j] gate[t,j]) / S   (renormalize != 0)
+ *   dlogits[t,e] = [e == idx_k] q_k p_e - p_e sum_k q_k p[idx_k]
+ *   dx[t,:] = sum_e dlogits[t,e] w_router[e,:]         (dt; NULL to skip)
+ *   dw_router[e,:] = sum_t dlogits[t,e] x[t,:]          (fp32 [E,H]; NULL to skip)
+ *   dbias[e] = sum_t dlogits[t,e]                       (fp32 [E]; NULL to skip)
+ *
+ * logits [T,E] are the fp32 logits moe_router_topk wrote (bias included),
+ * topk_idx [T,K] its selection (entries outside [0,E) get no gradient), dgate
+ * [T,K] fp32.  dlogits [T,E] fp32 is always written.  Sums over tokens are taken
+ * in a fixed order.  H a multiple of 8.  workspace: moe_router_backward_workspace_bytes
+ * (needed only if dw_router is given).
+ */
+size_t moe_router_backward_workspace_bytes(int T, int H, int E);
+moe_status_t moe_router_backward(const void* x, const void* w_router, const float* logits,
+                                 const int32_t* topk_idx, const float* dgate, int T, int H, int E,
+                                 int K, int renormalize, moe_dtype_t dt, float* dlogits, void* dx,
+                                 float* dw_router, float* dbias, void* workspace,
+                                 size_t workspace_bytes, moe_stream_t stream);
+
+/*
  * Backward of a3, the grouped SwiGLU expert FFN (bf16 only; Section 3.3: the
  * backward workflow mirrors the forward; f_e of Eq. 1 by the chain rule).  With
  * g = x_perm W_gate^T, u = x_perm W_up^T, s = 1/(1+e^-g), h = g s u, for every

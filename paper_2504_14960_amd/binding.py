@@ -68,6 +68,10 @@ def lib() -> C.CDLL:
     L.moe_unpermute_combine_backward.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, vp, vp]
     L.moe_permute_backward.restype = i
     L.moe_permute_backward.argtypes = [vp, vp, vp, i, i, i, i, i, vp, vp]
+    L.moe_router_backward_workspace_bytes.restype = sz
+    L.moe_router_backward_workspace_bytes.argtypes = [i, i, i]
+    L.moe_router_backward.restype = i
+    L.moe_router_backward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, sz, vp]
     L.moe_expert_backward_workspace_bytes.restype = sz
     L.moe_expert_backward_workspace_bytes.argtypes = [i, i, i, i]
     L.moe_expert_weights_transpose.restype = i
@@ -258,6 +262,23 @@ def expert_down_fp8(h: torch.Tensor, expert_offsets: torch.Tensor, w_down: torch
     E, H, _ = w_down.shape
     _check(lib().moe_expert_down_fp8(_ptr(h), _ptr(expert_offsets), R_max, H, F, E, _ptr(w_down), float(dq_down),
                                      _ptr(y_perm), _stream()))
+
+
+def router_backward_workspace_bytes(T: int, H: int, E: int) -> int:
+    return int(lib().moe_router_backward_workspace_bytes(T, H, E))
+
+
+def router_backward(x: torch.Tensor, w_router: torch.Tensor, logits: torch.Tensor, topk_idx: torch.Tensor,
+                    dgate: torch.Tensor, renormalize: bool, dlogits: torch.Tensor, dx: Optional[torch.Tensor],
+                    dw_router: Optional[torch.Tensor], dbias: Optional[torch.Tensor],
+                    workspace: Optional[torch.Tensor]) -> None:
+    T, E = logits.shape
+    K = topk_idx.shape[1]
+    H = x.shape[1]
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().moe_router_backward(_ptr(x), _ptr(w_router), _ptr(logits), _ptr(topk_idx), _ptr(dgate), T, H, E, K,
+                                     int(bool(renormalize)), _dt(x), _ptr(dlogits), _ptr(dx), _ptr(dw_router),
+                                     _ptr(dbias), _ptr(workspace), nbytes, _stream()))
 
 
 def expert_backward_workspace_bytes(R_max: int, H: int, F: int, E: int) -> int:

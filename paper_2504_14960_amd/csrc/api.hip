@@ -272,6 +272,48 @@ moe_status_t moe_permute_backward(const void* dx_perm, const int32_t* row_of_ass
     return check_launch(fn);
 }
 
+size_t moe_router_backward_workspace_bytes(int T, int H, int E) {
+    if (T < 0 || H <= 0 || E <= 0) return 0;
+    return router_backward_workspace_bytes(T, H, E);
+}
+
+moe_status_t moe_router_backward(const void* x, const void* w_router, const float* logits,
+                                 const int32_t* topk_idx, const float* dgate, int T, int H, int E,
+                                 int K, int renormalize, moe_dtype_t dt, float* dlogits, void* dx,
+                                 float* dw_router, float* dbias, void* workspace,
+                                 size_t workspace_bytes, moe_stream_t stream) {
+    static const char* fn = "moe_router_backward";
+    if (moe_status_t st = check_dims(fn, T, H, E, K, dt)) return st;
+    if (H % 8) return fail(MOE_ERR_UNSUPPORTED, "%s: H=%d must be a multiple of 8", fn, H);
+    if (T == 0) {
+        // no tokens: the sums over tokens are zero
+        if (dw_router) launch_fill_i32(reinterpret_cast<int32_t*>(dw_router), E * H, 0, 0, static_cast<hipStream_t>(stream));
+        if (dbias) launch_fill_i32(reinterpret_cast<int32_t*>(dbias), E, 0, 0, static_cast<hipStream_t>(stream));
+        return check_launch(fn);
+    }
+    REQUIRE_PTR(fn, logits);
+    REQUIRE_PTR(fn, topk_idx);
+    REQUIRE_PTR(fn, dgate);
+    REQUIRE_PTR(fn, dlogits);
+    if (dx) {
+        REQUIRE_PTR(fn, dx);
+        REQUIRE_PTR(fn, w_router);
+    }
+    if (dw_router) {
+        REQUIRE_PTR(fn, dw_router);
+        REQUIRE_PTR(fn, x);
+        const size_t need = router_backward_workspace_bytes(T, H, E);
+        if (workspace == nullptr || workspace_bytes < need)
+            return fail(MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                        workspace ? workspace_bytes : (size_t)0);
+        REQUIRE_PTR(fn, workspace);
+    }
+    if (dbias && (reinterpret_cast<uintptr_t>(dbias) & 3u)) return fail(MOE_ERR_INVALID_ARG, "%s: dbias is not 4-byte aligned", fn);
+    launch_router_backward(x, w_router, logits, topk_idx, dgate, T, H, E, K, renormalize != 0, dt, dlogits, dx,
+                           dw_router, dbias, workspace, static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
 struct BackwardLayout {
     size_t g, u, dh, dgdu, dy_t, h_t, dgdu_t, x_t, total;
     int rp_max;

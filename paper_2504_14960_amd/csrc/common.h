@@ -44,6 +44,12 @@ void launch_router(const void* x, const void* w, const float* bias, float* logit
                    int E, int K, int renorm, moe_dtype_t dt, int32_t* idx, float* gate,
                    hipStream_t s);
 
+// backward of the router: dlogits always; dx, dw, dbias where non-NULL; ws of router_backward_workspace_bytes
+size_t router_backward_workspace_bytes(int T, int H, int E);
+void launch_router_backward(const void* x, const void* w, const float* logits, const int32_t* idx, const float* dgate,
+                            int T, int H, int E, int K, int renorm, moe_dtype_t dt, float* dlogits, void* dx,
+                            float* dw, float* dbias, void* ws, hipStream_t s);
+
 // router: 16-token blocks per workgroup (1, 2 or 4); 0 = chosen from T and E
 void set_router_tile(int mb);
 

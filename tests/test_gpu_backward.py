@@ -141,3 +141,34 @@ def test_expert_ffn_backward_with_no_rows_gives_zero_weight_gradients():
     inp, offsets, R, x, dy, want = _ffn_backward_case(128, 128, 4, [0, 0, 0, 0], 8100)
     dx, dwg, dwu, dwd = _run_ffn_backward(inp, offsets, R, x, dy, r_pad=16)
     assert (values(dx) == 0).all() and (values(dwg) == 0).all() and (values(dwu) == 0).all() and (values(dwd) == 0).all()
+
+
+@pytest.mark.parametrize("T,H,E,K,renorm,bf16", [
+    (300, 256, 8, 2, True, True), (1000, 136, 16, 4, False, True), (257, 1032, 64, 8, False, True),
+    (130, 64, 256, 8, True, True), (200, 64, 8, 2, True, False), (33, 8, 1, 1, True, True),
+])
+def test_router_backward_against_oracle(T, H, E, K, renorm, bf16):
+    import torch
+    import paper_2504_14960_amd as moe
+    rng = np.random.default_rng(9000 + T)
+    x = make_tokens(9001 + T, T, H, bf16=bf16)
+    w = make_tokens(9002 + T, E, H, bf16=bf16, std=0.05)
+    logits32 = oracle.router_logits(x, w, None).astype(np.float32)
+    idx, _ = oracle.topk_gates(logits32, K, renorm)
+    dgate = rng.normal(size=(T, K)).astype(np.float32)
+    dl, dx, dw, db = oracle.router_backward(x, w, logits32, idx, dgate, renorm)
+    d_x, d_w = to_dev(x), to_dev(w)
+    g_dl = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    g_dx = torch.empty_like(d_x)
+    g_dw = torch.empty((E, H), dtype=torch.float32, device="cuda")
+    g_db = torch.empty((E,), dtype=torch.float32, device="cuda")
+    ws = torch.empty(moe.router_backward_workspace_bytes(T, H, E) + 256, dtype=torch.uint8, device="cuda")
+    moe.router_backward(d_x, d_w, to_dev(logits32), to_dev(idx), to_dev(dgate), renorm, g_dl, g_dx, g_dw, g_db, ws)
+    torch.cuda.synchronize()
+    # fp32 softmax Jacobian against fp64
+    np.testing.assert_allclose(g_dl.cpu().numpy(), dl, rtol=2e-4, atol=2e-6 * np.abs(dgate).max())
+    assert_close(to_host(g_dx), dx, bf16, "dx (router)")
+    # fp32 sums over T tokens of products with bf16/fp32 x
+    scale = np.abs(dw).max()
+    assert np.abs(g_dw.cpu().numpy() - dw).max() <= 2e-4 * scale + 1e-30
+    assert np.abs(g_db.cpu().numpy() - db).max() <= 2e-4 * np.abs(db).max() + 1e-6
