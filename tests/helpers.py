@@ -86,3 +86,19 @@ def capacity_rows(cfg) -> int:
     if cfg.capacity_factor is None:
         return 0
     return oracle.capacity(cfg.capacity_factor, cfg.T, cfg.K, cfg.E)
+
+
+def oracle_layer_backward(x, w_router, bias, w_gate, w_up, w_down, K, renorm, capacity, dy):
+    """The four backward functions chained in the order the backward workflow runs them (Section 3.3, mirrored)."""
+    E = w_router.shape[0]
+    T, H = x.shape
+    logits32 = oracle.router_logits(x, w_router, bias).astype(np.float32)
+    idx, gate = oracle.topk_gates(logits32, K, renorm)
+    perm = oracle.permute(x, idx, E, capacity)
+    R = perm.R
+    y_perm = oracle.experts(perm.x_perm, perm.offsets, w_gate, w_up, w_down)
+    dy_perm, dgate = oracle.combine_backward(dy, y_perm if R else np.zeros((1, H)), perm.row_of_assign, gate)
+    dx_perm, dwg, dwu, dwd = oracle.experts_backward(perm.x_perm, perm.offsets, w_gate, w_up, w_down, dy_perm)
+    dl, dx_r, dw_r, db = oracle.router_backward(x, w_router, logits32, idx, dgate, renorm)
+    dx = oracle.permute_backward(dx_perm if R else np.zeros((1, H)), perm.row_of_assign, T, K, addend=dx_r)
+    return dict(dx=dx, dw_router=dw_r, dbias=db, dw_gate=dwg, dw_up=dwu, dw_down=dwd, idx=idx)

@@ -172,3 +172,69 @@ def test_router_backward_against_oracle(T, H, E, K, renorm, bf16):
     scale = np.abs(dw).max()
     assert np.abs(g_dw.cpu().numpy() - dw).max() <= 2e-4 * scale + 1e-30
     assert np.abs(g_db.cpu().numpy() - db).max() <= 2e-4 * np.abs(db).max() + 1e-6
+
+
+@pytest.mark.parametrize("base,kw", [
+    ("mixtral8x22b", dict(T=640, H=256, F=384)),
+    ("tokendrop", dict(T=1536, H=256, F=256)),
+    ("mixtral8x7b", dict(T=300, H=128, F=128, K=1)),
+])
+def test_backward_of_the_whole_layer_chained_on_the_gpu(base, kw):
+    """Forward stage by stage (keeping what the backward needs), then the four backward calls in mirrored order,
+    against the oracle's chain (itself pinned against autograd of the whole layer)."""
+    import torch
+    import paper_2504_14960_amd as moe
+    from moe_inputs import get_config, make_layer_inputs
+    from helpers import capacity_rows, guard_margins, oracle_layer_backward
+    cfg = get_config(base).scaled(**kw)
+    inp = make_layer_inputs(cfg)
+    guard_margins(inp, cfg.K)
+    capacity = capacity_rows(cfg)
+    t = inp.tensors
+    T, H, E, K, F = cfg.T, cfg.H, cfg.E, cfg.K, cfg.F
+    dy = make_tokens(cfg.seed + 5, T, H, bf16=True)
+    want = oracle_layer_backward(t["x"], t["w_router"], inp.bias, t["w_gate"], t["w_up"], t["w_down"], K,
+                                 cfg.renormalize, capacity, values(dy))
+
+    d = {k: to_dev(v) for k, v in t.items()}
+    bias = None if inp.bias is None else to_dev(inp.bias)
+    r_max = moe.max_rows(T, K, E, capacity)
+    bf, i32, f32 = dict(dtype=torch.bfloat16, device="cuda"), dict(dtype=torch.int32, device="cuda"), dict(dtype=torch.float32, device="cuda")
+    logits, idx, gate = torch.empty((T, E), **f32), torch.empty((T, K), **i32), torch.empty((T, K), **f32)
+    counts, offsets = torch.empty((E,), **i32), torch.empty((E + 1,), **i32)
+    roa, aor = torch.empty((T * K,), **i32), torch.empty((r_max,), **i32)
+    pws = torch.empty((moe.permute_workspace_bytes(T, K, E) + 256,), dtype=torch.uint8, device="cuda")
+    x_perm, h, y_perm = torch.zeros((r_max, H), **bf), torch.zeros((r_max, F), **bf), torch.zeros((r_max, H), **bf)
+    y = torch.empty((T, H), **bf)
+    moe.router_topk(d["x"], d["w_router"], bias, logits, K, cfg.renormalize, idx, gate)
+    moe.permute(d["x"], idx, E, capacity, x_perm, counts, offsets, roa, aor, pws)
+    moe.grouped_gemm_swiglu(x_perm, offsets, d["w_gate"], d["w_up"], d["w_down"], h, y_perm)
+    moe.unpermute_combine(y_perm, roa, gate, None, y)
+    np.testing.assert_array_equal(to_host(idx), want["idx"])           # same routing on both sides
+
+    # ---- backward, mirrored ----
+    d_dy = to_dev(dy)
+    dy_perm, dgate = torch.zeros((r_max, H), **bf), torch.empty((T, K), **f32)
+    moe.unpermute_combine_backward(d_dy, y_perm, roa, gate, dy_perm, dgate)
+    wgu_t, wd_t = torch.empty((E, H, 2 * F), **bf), torch.empty((E, F, H), **bf)
+    moe.expert_weights_transpose(d["w_gate"], d["w_up"], d["w_down"], wgu_t, wd_t)
+    dx_perm = torch.zeros((r_max, H), **bf)
+    dwg, dwu, dwd = torch.empty((E, F, H), **bf), torch.empty((E, F, H), **bf), torch.empty((E, H, F), **bf)
+    ws = torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda")
+    moe.grouped_gemm_swiglu_backward(x_perm, h, dy_perm, offsets, d["w_gate"], d["w_up"], wgu_t, wd_t, dx_perm, dwg, dwu,
+                                     dwd, ws)
+    dlogits, dx_r = torch.empty((T, E), **f32), torch.empty((T, H), **bf)
+    dwr, dbias = torch.empty((E, H), **f32), torch.empty((E,), **f32)
+    rws = torch.empty(moe.router_backward_workspace_bytes(T, H, E) + 256, dtype=torch.uint8, device="cuda")
+    moe.router_backward(d["x"], d["w_router"], logits, idx, dgate, cfg.renormalize, dlogits, dx_r, dwr, dbias, rws)
+    dx = torch.empty((T, H), **bf)
+    moe.permute_backward(dx_perm, roa, dx_r, dx, K)
+    torch.cuda.synchronize()
+
+    _assert_grad_close(to_host(dx), want["dx"], "dx")
+    _assert_grad_close(to_host(dwg), want["dw_gate"], "dw_gate")
+    _assert_grad_close(to_host(dwu), want["dw_up"], "dw_up")
+    _assert_grad_close(to_host(dwd), want["dw_down"], "dw_down")
+    _assert_grad_close(dwr.cpu().numpy(), want["dw_router"], "dw_router")
+    if inp.bias is not None:
+        _assert_grad_close(dbias.cpu().numpy(), want["dbias"], "dbias")

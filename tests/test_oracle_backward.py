@@ -6,6 +6,7 @@ import pytest
 import torch
 
 import oracle
+from helpers import oracle_layer_backward
 
 
 def _routing(T, E, K, capacity, seed):
@@ -169,3 +170,43 @@ def test_router_backward_ignores_out_of_range_indices():
     idx_ok[bad] = 0
     dg_ok[bad] = 0.0          # an out-of-range slot behaves like a slot whose gate gradient is zero
     np.testing.assert_allclose(dl, oracle.router_backward(x, w, logits32, idx_ok, dg_ok, False)[0], rtol=1e-13, atol=1e-16)
+
+
+@pytest.mark.parametrize("K,renorm,capacity", [(2, True, 0), (2, False, 3), (1, True, 0), (3, True, 4)])
+def test_chained_backward_matches_autograd_of_the_whole_layer(K, renorm, capacity):
+    """Eq. 1 with Top-K gating, capacity drops and SwiGLU experts, written densely with torch fp64 ops (every expert
+    on every token, masked by the oracle's own routing decisions) and differentiated by autograd."""
+    rng = np.random.default_rng(50 + K)
+    T, H, E, F = 11, 6, 4, 5
+    x = rng.normal(0, 1, (T, H)).astype(np.float32)
+    wr = rng.normal(0, 0.5, (E, H)).astype(np.float32)
+    bias = rng.normal(0, 0.3, E).astype(np.float32)
+    wg = rng.normal(0, 0.4, (E, F, H)).astype(np.float32)
+    wu = rng.normal(0, 0.4, (E, F, H)).astype(np.float32)
+    wd = rng.normal(0, 0.4, (E, H, F)).astype(np.float32)
+    dy = rng.normal(size=(T, H))
+    got = oracle_layer_backward(x, wr, bias, wg, wu, wd, K, renorm, capacity, dy)
+    # routing decisions (piecewise constant) from the forward oracle
+    logits32 = oracle.router_logits(x, wr, bias).astype(np.float32)
+    idx, _ = oracle.topk_gates(logits32, K, renorm)
+    perm = oracle.permute(None, idx, E, capacity)
+    kept = torch.tensor(perm.row_of_assign.reshape(T, K) >= 0)
+
+    tx, twr, tb, twg, twu, twd = (torch.tensor(a.astype(np.float64), requires_grad=True) for a in (x, wr, bias, wg, wu, wd))
+    # the gating acts on the fp32-rounded logits; the gradient flows through the unrounded product
+    tl = tx @ twr.T + tb
+    tl = tl + (torch.tensor(logits32.astype(np.float64)) - tl).detach()
+    p = torch.softmax(tl, dim=1)
+    g = torch.gather(p, 1, torch.tensor(idx.astype(np.int64)))
+    if renorm:
+        g = g / g.sum(dim=1, keepdim=True)
+    y = torch.zeros((T, H), dtype=torch.float64)
+    for k in range(K):
+        for e in range(E):
+            sel = (torch.tensor(idx[:, k]) == e) & kept[:, k]
+            if sel.any():
+                f = (torch.nn.functional.silu(tx @ twg[e].T) * (tx @ twu[e].T)) @ twd[e].T
+                y = y + torch.where(sel[:, None], g[:, k:k + 1] * f, torch.zeros_like(f))
+    (y * torch.tensor(dy)).sum().backward()
+    for name, t in (("dx", tx), ("dw_router", twr), ("dbias", tb), ("dw_gate", twg), ("dw_up", twu), ("dw_down", twd)):
+        np.testing.assert_allclose(got[name], t.grad.numpy(), rtol=1e-9, atol=1e-12, err_msg=name)
