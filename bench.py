@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--ffn-backward", action="store_true",
                     help="also time the backward of the grouped expert FFN (and the one-off weight transposes it "
                          "needs) on the same routing; reported in a separate object, not part of the step")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time the backward of the whole layer (combine, expert FFN, router, permute backward in "
+                         "mirrored order) and report it under 'backward' (bf16 workloads without a shared expert)")
     ap.add_argument("--dispatch-backward", action="store_true",
                     help="also time the backward of the dispatcher's two data movements (combine backward, permute "
                          "backward) on the same routing; reported in a separate object, not part of the step")
@@ -330,7 +333,7 @@ def main():
         n_b, w_b = max(3, args.steps // 4), 2
         t_tr = timed(lambda: moe.expert_weights_transpose(w["w_gate"], w["w_up"], w["w_down"], wgu_t, wd_t), n_b, w_b)
         # y_perm stands in for the incoming gradient dy_perm (same shape and value range)
-        t_bw = timed(lambda: moe.grouped_gemm_swiglu_backward(s0["x_perm"], s0["h"], s0["y_perm"], s0["offsets"],
+        t_bw = timed(lambda: moe.grouped_gemm_swiglu_backward(s0["x_perm"], s0["h"], None, s0["y_perm"], s0["offsets"],
                                                               w["w_gate"], w["w_up"], wgu_t, wd_t, dxp, dwg, dwu, dwd,
                                                               bws), n_b, w_b)
         useful = 12.0 * R * H * F            # dh, dx (2 products), three weight gradients
@@ -341,6 +344,76 @@ def main():
             "weights_transpose_ms": round(t_tr, 4),
             "weights_transpose_gbs": round(2 * 3 * E * H * F * es / (t_tr * 1e-3) / 1e9, 1),
             "workspace_gb": round(bws.numel() / 1e9, 2)}
+    if args.backward and not fp8 and bf16 and not Fs:
+        s0 = sets[0]
+        bfk = dict(dtype=torch.bfloat16, device="cuda")
+        f32k = dict(dtype=torch.float32, device="cuda")
+        b = dict(wgu_t=torch.empty((E, H, 2 * F), **bfk), wd_t=torch.empty((E, F, H), **bfk),
+                 dwg=torch.empty((E, F, H), **bfk), dwu=torch.empty((E, F, H), **bfk), dwd=torch.empty((E, H, F), **bfk),
+                 gu=torch.empty((r_max, 2 * F), **bfk),
+                 dy_perm=torch.empty((r_max, H), **bfk), dx_perm=torch.empty((r_max, H), **bfk),
+                 dgate=torch.empty((T, K), **f32k), dlogits=torch.empty((T, E), **f32k),
+                 dx_r=torch.empty((T, H), **bfk), dx=torch.empty((T, H), **bfk),
+                 dwr=torch.empty((E, H), **f32k), dbias=torch.empty((E,), **f32k),
+                 ews=torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda"),
+                 rws=torch.empty(moe.router_backward_workspace_bytes(T, H, E) + 256, dtype=torch.uint8, device="cuda"))
+        bnames = ["weights_transpose", "combine_backward", "ffn_backward", "router_backward", "permute_backward"]
+
+        def bstep(ev=None):
+            def mark(i):
+                if ev is not None:
+                    ev[i].record()
+            mark(0)   # s0["y"] plays dy, the gradient of the layer output (same shape and value range)
+            moe.expert_weights_transpose(w["w_gate"], w["w_up"], w["w_down"], b["wgu_t"], b["wd_t"])
+            mark(1)
+            moe.unpermute_combine_backward(s0["y"], s0["y_perm"], s0["roa"], s0["gate"], b["dy_perm"], b["dgate"])
+            mark(2)
+            moe.grouped_gemm_swiglu_backward(s0["x_perm"], s0["h"], b["gu"], b["dy_perm"], s0["offsets"], w["w_gate"], w["w_up"],
+                                             b["wgu_t"], b["wd_t"], b["dx_perm"], b["dwg"], b["dwu"], b["dwd"], b["ews"])
+            mark(3)
+            moe.router_backward(s0["x"], w["w_router"], s0["logits"], s0["idx"], b["dgate"], cfg.renormalize,
+                                b["dlogits"], b["dx_r"], b["dwr"], b["dbias"], b["rws"])
+            mark(4)
+            moe.permute_backward(b["dx_perm"], s0["roa"], b["dx_r"], b["dx"], K)
+            mark(5)
+
+        def fstep():      # the training forward: as step(), the first GEMM also keeping g | u for the backward
+            moe.router_topk(s0["x"], w["w_router"], bias, s0["logits"], K, cfg.renormalize, s0["idx"], s0["gate"])
+            moe.permute(s0["x"], s0["idx"], E, capacity, s0["x_perm"], s0["counts"], s0["offsets"], s0["roa"],
+                        s0["aor"], s0["pws"])
+            moe.expert_gate_up_saving(s0["x_perm"], s0["offsets"], w["w_gate"], w["w_up"], s0["h"], b["gu"])
+            moe.expert_down(s0["h"], s0["offsets"], w["w_down"], s0["y_perm"])
+            moe.unpermute_combine(s0["y_perm"], s0["roa"], s0["gate"], None, s0["y"])
+
+        n_b = max(3, args.steps // 4)
+        for _ in range(2):
+            fstep()
+        torch.cuda.synchronize()
+        tf0 = time.perf_counter()
+        for i in range(n_b):
+            fstep()
+        torch.cuda.synchronize()
+        fms = (time.perf_counter() - tf0) * 1e3 / n_b
+        for _ in range(2):
+            bstep()
+        bev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_b)]
+        torch.cuda.synchronize()
+        tb0 = time.perf_counter()
+        for i in range(n_b):
+            bstep(bev[i])
+        torch.cuda.synchronize()
+        bms = (time.perf_counter() - tb0) * 1e3 / n_b
+        bst = {nm: round(sum(bev[i][j].elapsed_time(bev[i][j + 1]) for i in range(n_b)) / n_b, 4)
+               for j, nm in enumerate(bnames)}
+        useful = 12.0 * R * H * F
+        out["backward"] = {
+            "ms_per_step": round(bms, 4), "steps": n_b, "stage_ms": bst,
+            "forward_saving_gu_ms": round(fms, 4),
+            "tokens_per_s_fwd_bwd": round(T / ((fms + bms) * 1e-3), 1),
+            "ffn_backward_useful_tflops": round(useful / (bst["ffn_backward"] * 1e-3) / 1e12, 1),
+            "layer_useful_tflops_fwd_bwd": round(18.0 * R * H * F / ((fms + bms) * 1e-3) / 1e12, 1),
+            "note": "weights_transpose re-lays the three expert weight tensors once per optimizer step; "
+                    "with several micro-batches per step it is paid once, not per backward"}
     if args.dispatch_backward and not fp8:
         # dy plays the gradient of the layer output; the forward's y_perm, maps and gates are reused
         res = {}

@@ -232,9 +232,12 @@ moe_status_t moe_router_backward(const void* x, const void* w_router, const floa
  *   dw_gate[e] = dg^T x_perm    dw_up[e] = du^T x_perm
  *   dx_perm = dg W_gate[e] + du W_up[e]
  *
- * g and u are recomputed from x_perm (bf16, like every intermediate: g, u, dh,
- * dg, du are rounded to bf16 once each; accumulation is fp32); h is the
- * forward's.  The GEMM kernels multiply operands that are contiguous along the
+ * Every intermediate (g, u, dh, dg, du) is bf16, rounded once; accumulation is
+ * fp32; h is the forward's.  gu [R_max,2F] = (g | u) as written by
+ * moe_expert_gate_up_saving, the forward's first GEMM with the two
+ * pre-activations kept; gu == NULL makes the backward recompute g and u from
+ * x_perm, w_gate and w_up (two more GEMMs, no saved tensor; w_gate and w_up are
+ * read only then).  The GEMM kernels multiply operands that are contiguous along the
  * contraction index, so the weights are needed transposed:
  * moe_expert_weights_transpose writes wgu_t [E,H,2F] = (W_gate[e]^T | W_up[e]^T)
  * and wd_t [E,F,H] = W_down[e]^T; they stay valid until the weights change (all
@@ -249,7 +252,11 @@ size_t moe_expert_backward_workspace_bytes(int R_max, int H, int F, int E);
 moe_status_t moe_expert_weights_transpose(const void* w_gate, const void* w_up, const void* w_down,
                                           int H, int F, int E, void* wgu_t, void* wd_t,
                                           moe_stream_t stream);
-moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h, const void* dy_perm,
+moe_status_t moe_expert_gate_up_saving(const void* x_perm, const int32_t* expert_offsets, int R_max,
+                                       int H, int F, int E, const void* w_gate, const void* w_up,
+                                       void* h, void* gu, moe_stream_t stream);
+moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h, const void* gu,
+                                              const void* dy_perm,
                                               const int32_t* expert_offsets, int R_max, int H, int F,
                                               int E, const void* w_gate, const void* w_up,
                                               const void* wgu_t, const void* wd_t, void* dx_perm,

@@ -77,7 +77,9 @@ def lib() -> C.CDLL:
     L.moe_expert_weights_transpose.restype = i
     L.moe_expert_weights_transpose.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp]
     L.moe_grouped_gemm_swiglu_backward.restype = i
-    L.moe_grouped_gemm_swiglu_backward.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moe_grouped_gemm_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moe_expert_gate_up_saving.restype = i
+    L.moe_expert_gate_up_saving.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, vp, vp]
     L.moe_layer_workspace_bytes.restype = sz
     L.moe_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
     L.moe_layer_workspace_layout.restype = i
@@ -292,13 +294,21 @@ def expert_weights_transpose(w_gate: torch.Tensor, w_up: torch.Tensor, w_down: t
                                               _stream()))
 
 
-def grouped_gemm_swiglu_backward(x_perm: torch.Tensor, h: torch.Tensor, dy_perm: torch.Tensor,
-                                 expert_offsets: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor,
+def expert_gate_up_saving(x_perm: torch.Tensor, expert_offsets: torch.Tensor, w_gate: torch.Tensor,
+                          w_up: torch.Tensor, h: torch.Tensor, gu: torch.Tensor) -> None:
+    R_max, H = x_perm.shape
+    E, F, _ = w_gate.shape
+    _check(lib().moe_expert_gate_up_saving(_ptr(x_perm), _ptr(expert_offsets), R_max, H, F, E, _ptr(w_gate),
+                                           _ptr(w_up), _ptr(h), _ptr(gu), _stream()))
+
+
+def grouped_gemm_swiglu_backward(x_perm: torch.Tensor, h: torch.Tensor, gu: Optional[torch.Tensor],
+                                 dy_perm: torch.Tensor, expert_offsets: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor,
                                  wgu_t: torch.Tensor, wd_t: torch.Tensor, dx_perm: torch.Tensor, dw_gate: torch.Tensor,
                                  dw_up: torch.Tensor, dw_down: torch.Tensor, workspace: torch.Tensor) -> None:
     R_max, H = x_perm.shape
     E, F, _ = w_gate.shape
-    _check(lib().moe_grouped_gemm_swiglu_backward(_ptr(x_perm), _ptr(h), _ptr(dy_perm), _ptr(expert_offsets), R_max, H,
+    _check(lib().moe_grouped_gemm_swiglu_backward(_ptr(x_perm), _ptr(h), _ptr(gu), _ptr(dy_perm), _ptr(expert_offsets), R_max, H,
                                                   F, E, _ptr(w_gate), _ptr(w_up), _ptr(wgu_t), _ptr(wd_t),
                                                   _ptr(dx_perm), _ptr(dw_gate), _ptr(dw_up), _ptr(dw_down),
                                                   _ptr(workspace), workspace.numel() * workspace.element_size(),

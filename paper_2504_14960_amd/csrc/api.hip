@@ -365,7 +365,28 @@ moe_status_t moe_expert_weights_transpose(const void* w_gate, const void* w_up, 
     return check_launch(fn);
 }
 
-moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h, const void* dy_perm,
+moe_status_t moe_expert_gate_up_saving(const void* x_perm, const int32_t* expert_offsets, int R_max,
+                                       int H, int F, int E, const void* w_gate, const void* w_up,
+                                       void* h, void* gu, moe_stream_t stream) {
+    static const char* fn = "moe_expert_gate_up_saving";
+    if (R_max < 0 || H <= 0 || F <= 0 || E <= 0) return fail(MOE_ERR_INVALID_ARG, "%s: need R_max >= 0 and H, F, E > 0", fn);
+    if (E > kMaxExperts) return fail(MOE_ERR_UNSUPPORTED, "%s: E=%d exceeds the limit %d", fn, E, kMaxExperts);
+    if (!backward_supported(H, F)) return fail(MOE_ERR_UNSUPPORTED, "%s: H=%d and F=%d must be multiples of 128", fn, H, F);
+    if (R_max == 0) return MOE_OK;
+    REQUIRE_PTR(fn, x_perm);
+    REQUIRE_PTR(fn, expert_offsets);
+    REQUIRE_PTR(fn, w_gate);
+    REQUIRE_PTR(fn, w_up);
+    REQUIRE_PTR(fn, h);
+    REQUIRE_PTR(fn, gu);
+    if (!launch_gate_up_saving(x_perm, expert_offsets, R_max, H, F, E, w_gate, w_up, h, gu,
+                               static_cast<hipStream_t>(stream)))
+        return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
+    return check_launch(fn);
+}
+
+moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h, const void* gu,
+                                              const void* dy_perm,
                                               const int32_t* expert_offsets, int R_max, int H, int F,
                                               int E, const void* w_gate, const void* w_up,
                                               const void* wgu_t, const void* wd_t, void* dx_perm,
@@ -386,8 +407,12 @@ moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h,
         REQUIRE_PTR(fn, x_perm);
         REQUIRE_PTR(fn, h);
         REQUIRE_PTR(fn, dy_perm);
-        REQUIRE_PTR(fn, w_gate);
-        REQUIRE_PTR(fn, w_up);
+        if (gu == nullptr) {
+            REQUIRE_PTR(fn, w_gate);
+            REQUIRE_PTR(fn, w_up);
+        } else if (!aligned16(gu)) {
+            return fail(MOE_ERR_INVALID_ARG, "%s: gu is not 16-byte aligned", fn);
+        }
         REQUIRE_PTR(fn, wgu_t);
         REQUIRE_PTR(fn, wd_t);
         REQUIRE_PTR(fn, dx_perm);
@@ -398,12 +423,20 @@ moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h,
     }
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     if (R_max > 0) {
-        // recompute g and u; dh; the SwiGLU's derivative; the input gradient
-        bool ok = launch_grouped_nt(x_perm, expert_offsets, R_max, E, F, H, w_gate, ws + L.g, s);
-        ok = ok && launch_grouped_nt(x_perm, expert_offsets, R_max, E, F, H, w_up, ws + L.u, s);
+        // g and u (the forward's, or recomputed); dh; the SwiGLU's derivative; the input gradient
+        bool ok = true;
+        if (gu == nullptr) {
+            ok = launch_grouped_nt(x_perm, expert_offsets, R_max, E, F, H, w_gate, ws + L.g, s);
+            ok = ok && launch_grouped_nt(x_perm, expert_offsets, R_max, E, F, H, w_up, ws + L.u, s);
+        }
         ok = ok && launch_grouped_nt(dy_perm, expert_offsets, R_max, E, F, H, wd_t, ws + L.dh, s);
         if (!ok) return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
-        launch_swiglu_backward(ws + L.dh, ws + L.g, ws + L.u, expert_offsets + E, R_max, F, ws + L.dgdu, s);
+        if (gu)
+            launch_swiglu_backward(ws + L.dh, gu, static_cast<const uint8_t*>(gu) + (size_t)F * 2, (size_t)2 * F,
+                                   expert_offsets + E, R_max, F, ws + L.dgdu, s);
+        else
+            launch_swiglu_backward(ws + L.dh, ws + L.g, ws + L.u, (size_t)F, expert_offsets + E, R_max, F,
+                                   ws + L.dgdu, s);
         if (!launch_grouped_nt(ws + L.dgdu, expert_offsets, R_max, E, H, 2 * F, wgu_t, dx_perm, s))
             return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
         // operands of the weight gradients, transposed with every expert's rows as a zero-padded column segment

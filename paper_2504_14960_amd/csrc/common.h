@@ -86,9 +86,12 @@ void launch_transpose_batched(const void* src, int B, int R, int C, void* dst, s
 // dst [C, rp_max]: rows of expert e of src [rows, C] become the columns of its zero-padded segment
 void launch_ragged_transpose(const void* src, const int32_t* offsets, int E, int C, int rp_max, void* dst,
                              hipStream_t s);
-// out [rows, 2F] = dg | du from dh, g, u [rows, F]; rows = *n_rows (device)
-void launch_swiglu_backward(const void* dh, const void* g, const void* u, const int32_t* n_rows, int r_max, int F,
-                            void* out, hipStream_t s);
+// out [rows, 2F] = dg | du from dh [rows, F] and g, u (rows ld_gu elements apart); rows = *n_rows (device)
+void launch_swiglu_backward(const void* dh, const void* g, const void* u, size_t ld_gu, const int32_t* n_rows,
+                            int r_max, int F, void* out, hipStream_t s);
+// the forward's gate/up GEMM that also stores the pre-activations g | u to gu [rows, 2F]; false if not covered
+bool launch_gate_up_saving(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                           const void* w_gate, const void* w_up, void* h, void* gu, hipStream_t s);
 // dw [E, M, N] = per expert a_t[:, seg_e] . b_t[:, seg_e]^T over the expert's padded column segment
 void launch_wgrad_gemm(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
                        void* dw, hipStream_t s);

@@ -107,12 +107,12 @@ __global__ __launch_bounds__(256) void ragged_transpose_kernel(const uint16_t* _
     store_tile_t(dst, ldo, c0, C, (size_t)p0, TT, tile);
 }
 
-// dg | du from dh, g, u (all [rows, F] bf16; out [rows, 2F]): with s = 1/(1+e^-g),
+// dg | du from dh [rows, F] and g, u (bf16, rows ld_gu elements apart; out [rows, 2F]): with s = 1/(1+e^-g),
 //   du = dh * g * s,   dg = dh * u * s * (1 + g * (1 - s)).
 // Only rows below *n_rows (device: the kept-row count) are processed.
 __global__ __launch_bounds__(256) void swiglu_backward_kernel(const uint16_t* __restrict__ dh,
                                                               const uint16_t* __restrict__ g,
-                                                              const uint16_t* __restrict__ u,
+                                                              const uint16_t* __restrict__ u, size_t ld_gu,
                                                               const int32_t* __restrict__ n_rows, int F,
                                                               uint16_t* __restrict__ out) {
     const int rows = *n_rows;
@@ -122,8 +122,8 @@ __global__ __launch_bounds__(256) void swiglu_backward_kernel(const uint16_t* __
         const size_t r = i / vpr;
         const int c = (int)(i - r * vpr) * 8;
         const u32x4 a = *reinterpret_cast<const u32x4*>(dh + r * F + c);
-        const u32x4 b = *reinterpret_cast<const u32x4*>(g + r * F + c);
-        const u32x4 d = *reinterpret_cast<const u32x4*>(u + r * F + c);
+        const u32x4 b = *reinterpret_cast<const u32x4*>(g + r * ld_gu + c);
+        const u32x4 d = *reinterpret_cast<const u32x4*>(u + r * ld_gu + c);
         u32x4 og, ou;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -162,14 +162,14 @@ void launch_ragged_transpose(const void* src, const int32_t* offsets, int E, int
                        (size_t)rp_max);
 }
 
-void launch_swiglu_backward(const void* dh, const void* g, const void* u, const int32_t* n_rows, int r_max, int F,
-                            void* out, hipStream_t s) {
+void launch_swiglu_backward(const void* dh, const void* g, const void* u, size_t ld_gu, const int32_t* n_rows,
+                            int r_max, int F, void* out, hipStream_t s) {
     if (r_max <= 0) return;
     size_t blocks = ((size_t)r_max * (F / 8) + 255) / 256;
     if (blocks > 256 * 16) blocks = 256 * 16;
     hipLaunchKernelGGL(swiglu_backward_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                        static_cast<const uint16_t*>(dh), static_cast<const uint16_t*>(g),
-                       static_cast<const uint16_t*>(u), n_rows, F, static_cast<uint16_t*>(out));
+                       static_cast<const uint16_t*>(u), ld_gu, n_rows, F, static_cast<uint16_t*>(out));
 }
 
 }  // namespace moe

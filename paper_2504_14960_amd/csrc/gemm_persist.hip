@@ -52,10 +52,16 @@ namespace {
 // columns) into a private patch of W = 64*FO bytes per row, 16-byte granules
 // XOR-swizzled by the row so that neither side has bank conflicts, reads them
 // back as whole 16-byte granules along the rows and stores those.
-template <int FM, int FN, int WM, bool SWIGLU, bool ACC_IN_AGPR>
+//
+// MODE 0: C = acc.  MODE 1: C = silu(gate) * up, the gate in the first half of
+// the fragments and the up projection in the second.  MODE 2: as 1, and the
+// two pre-activations themselves go to GU [rows, 2N] (gate in columns
+// [0, N), up in [N, 2N)) for a backward pass that does not recompute them.
+template <int FM, int FN, int WM, int MODE, bool ACC_IN_AGPR>
 __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_row0, int t_rows, int t_n0,
-                                                  bf16_t* __restrict__ C, int N, int wm, int wn, int lane,
-                                                  uint8_t* stage) {
+                                                  bf16_t* __restrict__ C, bf16_t* __restrict__ GU, int N, int wm,
+                                                  int wn, int lane, uint8_t* stage) {
+    constexpr bool SWIGLU = MODE != 0;
     constexpr int FO = SWIGLU ? FN / 2 : FN;
     constexpr int W = FO * 64;        // bytes per staged row
     constexpr int GPR = W / 16;       // granules per row
@@ -81,6 +87,33 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_r
         if (ACC_IN_AGPR) {
 #pragma unroll
             for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
+        }
+        if (MODE == 2) {
+            // the pre-activations first: gate half, then up half, each through the same patch
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+#pragma unroll
+                for (int j = 0; j < FO; ++j) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x16& a = acc[i][j + half * FO];
+                        u32x2 o;
+                        o[0] = pack2_bf16(a[4 * q], a[4 * q + 1]);
+                        o[1] = pack2_bf16(a[4 * q + 2], a[4 * q + 3]);
+                        *reinterpret_cast<u32x2*>(wrow + (((4 * j + q) ^ xw) << 4)) = o;
+                    }
+                }
+#pragma unroll
+                for (int it = 0; it < 32 / RPI; ++it) {
+                    const int row = it * RPI + rl;
+                    const int xr = (row / RP256) & (GPR - 1);
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * W + ((gl ^ xr) << 4));
+                    const int grow = wm * WM + i * 32 + row;
+                    if (grow < t_rows && col < N)
+                        *reinterpret_cast<u32x4*>(GU + (size_t)(t_row0 + grow) * (2 * N) + half * N + col) = v;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
 #pragma unroll
         for (int j = 0; j < FO; ++j) {
@@ -116,10 +149,12 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_r
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+template <int BM, int BN, int WGM, int WGN, int MODE>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
-    const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, int ntn) {
+    const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, bf16_t* __restrict__ GU,
+    int ntn) {
+    constexpr bool SWIGLU = MODE != 0;
     constexpr int BK = 64;
     constexpr int NW = WGM * WGN;
     constexpr int NT = NW * 64;
@@ -367,7 +402,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         // Epilogue.  The activation slot that held the last k-tile (now l2) is
         // idle: every wave finished reading it before the last barrier, and the
         // next loads into it are issued only after the barrier below.
-        store_tile_staged<FM, FN, WM, SWIGLU, (FM * FN * 16 > 128)>(acc, c_row0, c_rows, c_n0, C, N, wm, wn, lane,
+        store_tile_staged<FM, FN, WM, MODE, (FM * FN * 16 > 128)>(acc, c_row0, c_rows, c_n0, C, GU, N, wm, wn, lane,
                                               a_region + l2 + wave * (32 * FO * 64));
         if (!n_valid) break;
         c_a = n_a; c_b0 = n_b0; c_b1 = n_b1; c_alim = n_alim; c_blim = n_blim;
@@ -401,13 +436,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
 #endif
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+template <int BM, int BN, int WGM, int WGN, int MODE>
 void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B0,
-                    const void* B1, void* C, hipStream_t s) {
-    constexpr int OUTN = SWIGLU ? BN / 2 : BN;
+                    const void* B1, void* C, void* GU, hipStream_t s) {
+    constexpr int OUTN = MODE != 0 ? BN / 2 : BN;
     constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
     const int ntn = (N + OUTN - 1) / OUTN;
-    auto kern = gemm_bf16_persist_kernel<BM, BN, WGM, WGN, SWIGLU>;
+    auto kern = gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -418,15 +453,15 @@ void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int
     const int grid = min(persist_grid(), grid_for(r_max, E, BM, ntn));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A), offsets, E, N,
                        K, static_cast<const bf16_t*>(B0), static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C),
-                       ntn);
+                       static_cast<bf16_t*>(GU), ntn);
 }
 
 template <int BM, int BN, int WGM, int WGN>
 void run_persist_pair(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                       const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm, int phase,
                       hipStream_t s) {
-    if (phase & 1) launch_persist<BM, BN, WGM, WGN, true>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, s);
-    if (phase & 2) launch_persist<BM, BN, WGM, WGN, false>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, s);
+    if (phase & 1) launch_persist<BM, BN, WGM, WGN, 1>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, nullptr, s);
+    if (phase & 2) launch_persist<BM, BN, WGM, WGN, 0>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, nullptr, s);
 }
 
 }  // namespace
@@ -438,7 +473,15 @@ void set_persist_workgroups(int n) { g_persist_workgroups = n; }
 bool launch_grouped_nt(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B,
                        void* C, hipStream_t s) {
     if (K < 128 || K % 64 || N % 8) return false;
-    launch_persist<256, 256, 2, 4, false>(A, offsets, r_max, E, N, K, B, nullptr, C, s);
+    launch_persist<256, 256, 2, 4, 0>(A, offsets, r_max, E, N, K, B, nullptr, C, nullptr, s);
+    return true;
+}
+
+// h = silu(x W_gate^T) * (x W_up^T) as in the forward, and the two pre-activations to gu [rows, 2F]
+bool launch_gate_up_saving(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
+                           const void* w_gate, const void* w_up, void* h, void* gu, hipStream_t s) {
+    if (H < 128 || H % 64 || F % 8) return false;
+    launch_persist<256, 256, 2, 4, 2>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, gu, s);
     return true;
 }
 

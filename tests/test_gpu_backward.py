@@ -76,7 +76,7 @@ def _ffn_backward_case(H, F, E, counts, seed):
     return inp, offsets, R, x, dy, want
 
 
-def _run_ffn_backward(inp, offsets, R, x, dy, r_pad=0):
+def _run_ffn_backward(inp, offsets, R, x, dy, r_pad=0, saved=False):
     import torch
     import paper_2504_14960_amd as moe
     E, F, H = inp["w_gate"].shape
@@ -90,14 +90,32 @@ def _run_ffn_backward(inp, offsets, R, x, dy, r_pad=0):
     off = to_dev(offsets)
     h = torch.zeros((r_max, F), **bf)
     y = torch.zeros((r_max, H), **bf)
-    moe.grouped_gemm_swiglu(dx_in, off, wg, wu, wd, h, y)          # the forward leaves h behind
+    gu = None
+    if saved:
+        # the forward that keeps the pre-activations: h must be the plain forward's bit for bit, gu = (g | u)
+        gu = torch.zeros((r_max, 2 * F), **bf)
+        h_plain = torch.zeros((r_max, F), **bf)
+        moe.expert_gate_up(dx_in, off, wg, wu, h_plain)
+        moe.expert_gate_up_saving(dx_in, off, wg, wu, h, gu)
+        moe.expert_down(h, off, wd, y)
+        torch.cuda.synchronize()
+        assert torch.equal(h, h_plain)
+        got_gu = to_host(gu)
+        assert (values(got_gu)[R:] == 0).all()
+        for e in range(E):
+            lo, hi = int(offsets[e]), int(offsets[e + 1])
+            if hi > lo:     # x W^T is the router's linear map with another weight matrix
+                assert_close(got_gu[lo:hi, :F], oracle.router_logits(x[lo:hi], inp["w_gate"][e], None), True, f"g of expert {e}")
+                assert_close(got_gu[lo:hi, F:], oracle.router_logits(x[lo:hi], inp["w_up"][e], None), True, f"u of expert {e}")
+    else:
+        moe.grouped_gemm_swiglu(dx_in, off, wg, wu, wd, h, y)          # the forward leaves h behind
     wgu_t = torch.empty((E, H, 2 * F), **bf)
     wd_t = torch.empty((E, F, H), **bf)
     moe.expert_weights_transpose(wg, wu, wd, wgu_t, wd_t)
     dxp = torch.zeros((r_max, H), **bf)
     dwg, dwu, dwd = torch.full((E, F, H), 7.0, **bf), torch.full((E, F, H), 7.0, **bf), torch.full((E, H, F), 7.0, **bf)
     ws = torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda")
-    moe.grouped_gemm_swiglu_backward(dx_in, h, dy_in, off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
+    moe.grouped_gemm_swiglu_backward(dx_in, h, gu, dy_in, off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
     torch.cuda.synchronize()
     # the transposes are plain copies: check them bit for bit against the host
     np.testing.assert_array_equal(to_host(wd_t), np.ascontiguousarray(inp["w_down"].transpose(0, 2, 1)))
@@ -122,11 +140,12 @@ def _assert_grad_close(got, ref, what):
     (128, 128, 3, [64, 130, 5]),                   # smallest supported sizes
     (384, 256, 64, None),                          # many small experts
 ])
-def test_expert_ffn_backward_against_oracle(H, F, E, counts):
+@pytest.mark.parametrize("saved", [False, True], ids=["recompute", "saved_gu"])
+def test_expert_ffn_backward_against_oracle(H, F, E, counts, saved):
     if counts is None:
         counts = np.random.default_rng(12).integers(0, 90, size=E).tolist()
     inp, offsets, R, x, dy, want = _ffn_backward_case(H, F, E, counts, 8000 + H + E)
-    dx, dwg, dwu, dwd = _run_ffn_backward(inp, offsets, R, x, dy, r_pad=9)
+    dx, dwg, dwu, dwd = _run_ffn_backward(inp, offsets, R, x, dy, r_pad=9, saved=saved)
     assert (values(dx)[R:] == 0).all()                     # rows past the kept ones untouched
     _assert_grad_close(dx[:R], want[0], "dx_perm")
     _assert_grad_close(dwg, want[1], "dw_gate")
@@ -208,7 +227,9 @@ def test_backward_of_the_whole_layer_chained_on_the_gpu(base, kw):
     y = torch.empty((T, H), **bf)
     moe.router_topk(d["x"], d["w_router"], bias, logits, K, cfg.renormalize, idx, gate)
     moe.permute(d["x"], idx, E, capacity, x_perm, counts, offsets, roa, aor, pws)
-    moe.grouped_gemm_swiglu(x_perm, offsets, d["w_gate"], d["w_up"], d["w_down"], h, y_perm)
+    gu = torch.zeros((r_max, 2 * F), **bf)
+    moe.expert_gate_up_saving(x_perm, offsets, d["w_gate"], d["w_up"], h, gu)
+    moe.expert_down(h, offsets, d["w_down"], y_perm)
     moe.unpermute_combine(y_perm, roa, gate, None, y)
     np.testing.assert_array_equal(to_host(idx), want["idx"])           # same routing on both sides
 
@@ -221,7 +242,7 @@ def test_backward_of_the_whole_layer_chained_on_the_gpu(base, kw):
     dx_perm = torch.zeros((r_max, H), **bf)
     dwg, dwu, dwd = torch.empty((E, F, H), **bf), torch.empty((E, F, H), **bf), torch.empty((E, H, F), **bf)
     ws = torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda")
-    moe.grouped_gemm_swiglu_backward(x_perm, h, dy_perm, offsets, d["w_gate"], d["w_up"], wgu_t, wd_t, dx_perm, dwg, dwu,
+    moe.grouped_gemm_swiglu_backward(x_perm, h, gu, dy_perm, offsets, d["w_gate"], d["w_up"], wgu_t, wd_t, dx_perm, dwg, dwu,
                                      dwd, ws)
     dlogits, dx_r = torch.empty((T, E), **f32), torch.empty((T, H), **bf)
     dwr, dbias = torch.empty((E, H), **f32), torch.empty((E,), **f32)

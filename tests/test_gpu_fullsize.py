@@ -255,14 +255,15 @@ def test_full_size_ffn_backward(name):
     wg, wu, wd = to_dev(t["w_gate"]), to_dev(t["w_up"]), to_dev(t["w_down"])
     h = torch.empty((r_max, F), **bf)
     y = torch.empty((r_max, H), **bf)
-    moe.grouped_gemm_swiglu(d_x, off, wg, wu, wd, h, y)
+    gu = torch.empty((r_max, 2 * F), **bf)
+    moe.expert_gate_up_saving(d_x, off, wg, wu, h, gu)       # the forward that keeps g | u for the backward
     del y
     wgu_t, wd_t = torch.empty((E, H, 2 * F), **bf), torch.empty((E, F, H), **bf)
     moe.expert_weights_transpose(wg, wu, wd, wgu_t, wd_t)
     dxp = torch.empty((r_max, H), **bf)
     dwg, dwu, dwd = torch.empty((E, F, H), **bf), torch.empty((E, F, H), **bf), torch.empty((E, H, F), **bf)
     ws = torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda")
-    moe.grouped_gemm_swiglu_backward(d_x, h, d_dy, off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
+    moe.grouped_gemm_swiglu_backward(d_x, h, gu, d_dy, off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
     torch.cuda.synchronize()
 
     def close(got, ref, what):     # the gradient bar of tests/test_gpu_backward.py
