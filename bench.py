@@ -54,6 +54,8 @@ def parse_args():
                     help="also time the backward of the dispatcher's two data movements (combine backward, permute "
                          "backward) on the same routing; reported in a separate object, not part of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="skip the bare-MFMA probe (what this box sustains on zero and on workload-like operands)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (scale reference for rocprofv3's "
@@ -309,6 +311,34 @@ def main():
         "context": "the paper reports 49.3 % (Mixtral 8x22B) and 39.0 % (Qwen2-57B-A14B) MFU for whole training "
                    "steps on H100 clusters: other hardware, other scope, shown for orientation only",
     }
+    if not args.no_probe and bf16 and not fp8:
+        # the bare inner loop of the grouped GEMM (MFMA + LDS fragment reads, nothing else) on this machine, with
+        # all-zero operands and with operands distributed like the workload's: the second is what power
+        # management lets dense bf16 MFMA sustain here, the practical ceiling under roofline.peak
+        from moe_inputs import make_tokens
+        nwg, iters = 256, 20000
+        sink = torch.empty(nwg * 256, dtype=torch.float32, device="cuda")
+        ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
+        images = {"zeros": np.zeros((512, 64), dtype=np.uint16),
+                  "workload_like": np.concatenate([make_tokens(4242, 256, 64, True, 1.0),
+                                                   make_tokens(4243, 256, 64, True, 0.02)])}
+        probe = {}
+        for nm, img in images.items():
+            d_img = dev(np.ascontiguousarray(img))
+            moe.probe_mfma_bf16(d_img, iters // 10, nwg, sink, ticks)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            moe.probe_mfma_bf16(d_img, iters, nwg, sink, ticks)
+            e1.record()
+            torch.cuda.synchronize()
+            tk = ticks.cpu().tolist()
+            probe[nm] = {"tflops": round(nwg * iters * 8388608.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1),
+                         "shader_mhz": round(100.0 * tk[0] / max(tk[1], 1), 0)}
+        probe["note"] = ("bare 32x32x16 bf16 MFMA + LDS fragment loop, 256 workgroups x 4 waves, no global traffic: "
+                         "the rate and clock this box sustains; operands ~N(0,1) x N(0,0.02^2) as in the workload")
+        roofline["mfma_probe"] = probe
+        roofline["frac_of_probe"] = round(dom["achieved"] / probe["workload_like"]["tflops"], 4)
     if args.ffn_backward and not fp8 and bf16:
         s0 = sets[0]
         bfk = dict(dtype=torch.bfloat16, device="cuda")

@@ -361,6 +361,22 @@ moe_status_t moe_expert_down_fp8(const void* h_fp8, const int32_t* expert_offset
                                  int F, int E, const void* w_down_fp8, float dq_down,
                                  void* y_perm_bf16, moe_stream_t stream);
 
+/*
+ * Measurement probe (not a stage of the layer; for callers that cannot measure
+ * the chip's sustained matrix rate otherwise, e.g. bench.py's roofline note).
+ * Runs the bare inner loop of the bf16 grouped GEMM: `workgroups` workgroups of
+ * four waves, each wave a 128 x 128 accumulator block, LDS fragment reads and
+ * 32x32x16 bf16 MFMAs over a 64 KiB operand image, nothing else.  image: 65536
+ * bytes, two blocks of [256 rows][64 bf16] (first operand, second operand).
+ * One launch executes workgroups * iters * 8388608 FLOP.  sink: workgroups*256
+ * floats (written, meaningless).  ticks (may be NULL): 2 x uint64, shader
+ * clocks and 100 MHz reference clocks spent by workgroup 0 in its loop, i.e.
+ * ticks[0] / ticks[1] * 100 = the shader clock in MHz under this load.
+ * Enqueues one kernel; the caller times it.  1 <= iters, 1 <= workgroups <= 65536.
+ */
+moe_status_t moe_probe_mfma_bf16(const void* image, int iters, int workgroups, float* sink,
+                                 uint64_t* ticks, moe_stream_t stream);
+
 /* Tuning knobs for experiments (process-wide, not thread-safe; defaults are
  * the tuned ones).  Unknown names return MOE_ERR_INVALID_ARG.  Names:
  * "gemm_variant" (0 = auto); "gemm_workgroups" (workgroups launched by the

@@ -78,6 +78,8 @@ def lib() -> C.CDLL:
     L.moe_expert_weights_transpose.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp]
     L.moe_grouped_gemm_swiglu_backward.restype = i
     L.moe_grouped_gemm_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moe_probe_mfma_bf16.restype = i
+    L.moe_probe_mfma_bf16.argtypes = [vp, i, i, vp, vp, vp]
     L.moe_expert_gate_up_saving.restype = i
     L.moe_expert_gate_up_saving.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, vp, vp]
     L.moe_layer_workspace_bytes.restype = sz
@@ -328,6 +330,12 @@ def permute_backward(dx_perm: torch.Tensor, row_of_assign: torch.Tensor, addend:
     T, H = dx.shape
     _check(lib().moe_permute_backward(_ptr(dx_perm), _ptr(row_of_assign), _ptr(addend), T, H, K, dx_perm.shape[0],
                                       _dt(dx), _ptr(dx), _stream()))
+
+
+def probe_mfma_bf16(image: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor,
+                    ticks: Optional[torch.Tensor]) -> None:
+    assert image.numel() * image.element_size() == 65536 and sink.numel() >= workgroups * 256
+    _check(lib().moe_probe_mfma_bf16(_ptr(image), iters, workgroups, _ptr(sink), _ptr(ticks), _stream()))
 
 
 def layer_workspace_bytes(T: int, H: int, E: int, K: int, F: int, Fs: int, capacity: int, dtype: int) -> int:

@@ -96,6 +96,10 @@ bool launch_gate_up_saving(const void* x_perm, const int32_t* offsets, int r_max
 void launch_wgrad_gemm(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
                        void* dw, hipStream_t s);
 
+// measurement probe: the bare bf16 MFMA + LDS-fragment loop over a 64 KiB operand image
+void launch_probe_mfma_bf16(const void* image, int iters, int workgroups, float* sink, unsigned long long* ticks,
+                            hipStream_t s);
+
 // FP8 (E4M3) path of the expert FFN: per-tensor quantisation with amax, and the
 // two grouped GEMMs on quantised operands (phase bits as above)
 void launch_fp8_quantize(const void* src, moe_dtype_t dt, size_t n, float scale, void* dst, float* amax,
