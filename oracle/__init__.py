@@ -26,6 +26,7 @@ def lib() -> C.CDLL:
         L.oracle_capacity.restype = C.c_int
         L.oracle_capacity.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int]
         L.oracle_permute.restype = C.c_int
+        L.oracle_permute_variant.restype = C.c_int
         L.oracle_layer_forward.restype = C.c_int
         L.oracle_fp8_decode.restype = C.c_double
         L.oracle_fp8_decode.argtypes = [C.c_uint8]
@@ -122,6 +123,40 @@ def permute(x: Optional[np.ndarray], idx: np.ndarray, E: int, capacity_rows: int
     aor = np.empty(max(r_max, 1), dtype=np.int32)
     R = lib().oracle_permute(_p(x), _p(idx), T, H, E, K, int(capacity_rows), dt, r_max,
                              _p(x_perm), _p(counts), _p(offsets), _p(roa), _p(aor))
+    return Permutation(int(R), x_perm, counts, offsets, roa, aor[:r_max])
+
+
+def permute_variant(x: Optional[np.ndarray], idx: np.ndarray, scores: Optional[np.ndarray], E: int,
+                    capacity_rows: int, by_score: bool, pad: bool, r_max: Optional[int] = None,
+                    H: Optional[int] = None) -> Permutation:
+    """Dispatch with the drop rule (position or score) and layout (packed or padded to capacity) chosen."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    T, K = idx.shape
+    if scores is not None:
+        scores = np.ascontiguousarray(scores, dtype=np.float32)
+        assert scores.shape == (T, K)
+    assert not by_score or scores is not None
+    assert not pad or capacity_rows > 0
+    if x is not None:
+        assert x.shape[0] == T
+        H = x.shape[1]
+        dt = _dt(x)
+    else:
+        H = H or 1
+        dt = 0
+    if r_max is None:
+        if pad:
+            r_max = E * capacity_rows
+        else:
+            r_max = T * K if capacity_rows <= 0 else min(T * K, E * capacity_rows)
+    x_perm = np.zeros((r_max, H), dtype=x.dtype) if x is not None else None
+    counts = np.empty(E, dtype=np.int32)
+    offsets = np.empty(E + 1, dtype=np.int32)
+    roa = np.empty(T * K, dtype=np.int32)
+    aor = np.empty(max(r_max, 1), dtype=np.int32)
+    R = lib().oracle_permute_variant(_p(x), _p(idx), _p(scores), T, H, E, K, int(capacity_rows), int(by_score),
+                                     int(pad), dt, r_max, _p(x_perm), _p(counts), _p(offsets), _p(roa), _p(aor))
+    assert R >= 0
     return Permutation(int(R), x_perm, counts, offsets, roa, aor[:r_max])
 
 

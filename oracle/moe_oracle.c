@@ -200,6 +200,82 @@ int oracle_permute(const void* x, const int32_t* idx, int T, int H, int E, int K
     return R;
 }
 
+/* ---- variants of the local dispatch: which assignments an over-subscribed
+ * expert drops, and whether every expert's block is padded to the capacity.
+ * (Eq. 4 fixes the capacity; the paper's benchmark drops by position.  These two
+ * variants are the other drop rule and the fixed-shape layout of capacity-based
+ * MoE training.)
+ *
+ * by_score = 0: an expert keeps its first `capacity` assignments in assignment
+ *   order (as oracle_permute).
+ * by_score = 1: it keeps the `capacity` assignments with the largest score
+ *   (scores [T,K] float, compared as floats; equal scores: the lower assignment
+ *   index is better).
+ * Either way the kept rows of an expert are laid out in ascending assignment
+ * index.
+ * pad = 0: experts packed back to back (offsets = running sum of the counts).
+ * pad = 1: expert e owns rows [e*capacity, (e+1)*capacity): offsets[e] =
+ *   e*capacity, counts[e] = rows really kept, the rest of the block is zero rows
+ *   with assign_of_row = -1.  Needs capacity > 0 and r_max >= E*capacity.
+ * Returns offsets[E]. */
+typedef struct { float score; int32_t a; } scored_t;
+
+static int better_first(const void* pa, const void* pb) {
+    const scored_t* a = (const scored_t*)pa;
+    const scored_t* b = (const scored_t*)pb;
+    if (a->score > b->score) return -1;
+    if (a->score < b->score) return 1;
+    return (a->a > b->a) - (a->a < b->a);
+}
+
+int oracle_permute_variant(const void* x, const int32_t* idx, const float* scores, int T, int H,
+                           int E, int K, int capacity, int by_score, int pad, int dt, int r_max,
+                           void* x_perm, int32_t* counts, int32_t* offsets,
+                           int32_t* row_of_assign, int32_t* assign_of_row) {
+    const size_t row_bytes = (size_t)H * elem_size(dt);
+    const size_t A = (size_t)T * K;
+    if (pad && capacity <= 0) return -1;
+    char* keep = (char*)calloc(A + 1, 1);
+    scored_t* list = (scored_t*)malloc(sizeof(scored_t) * (A + 1));
+    for (size_t a = 0; a < A; ++a) row_of_assign[a] = -1;
+    for (int r = 0; r < r_max; ++r) assign_of_row[r] = -1;
+    if (x_perm && pad) memset(x_perm, 0, (size_t)r_max * row_bytes);
+    /* the kept set, expert by expert */
+    for (int e = 0; e < E; ++e) {
+        size_t n = 0;
+        for (size_t a = 0; a < A; ++a)
+            if (idx[a] == e) {
+                list[n].score = (by_score && scores) ? scores[a] : 0.0f;
+                list[n].a = (int32_t)a;
+                ++n;
+            }
+        /* by position: all scores equal, so the order below is the assignment order */
+        qsort(list, n, sizeof(scored_t), better_first);
+        size_t kept = (capacity > 0 && n > (size_t)capacity) ? (size_t)capacity : n;
+        for (size_t i = 0; i < kept; ++i) keep[list[i].a] = 1;
+        counts[e] = (int32_t)kept;
+    }
+    offsets[0] = 0;
+    for (int e = 0; e < E; ++e) offsets[e + 1] = pad ? (e + 1) * capacity : offsets[e] + counts[e];
+    /* rows: kept assignments of an expert in ascending assignment index */
+    int32_t* next = (int32_t*)calloc((size_t)E, sizeof(int32_t));
+    for (size_t a = 0; a < A; ++a) {
+        if (!keep[a]) continue;
+        const int e = idx[a];
+        const int row = (pad ? e * capacity : offsets[e]) + next[e]++;
+        if (row >= r_max) continue; /* inconsistent r_max: never an address */
+        row_of_assign[a] = row;
+        assign_of_row[row] = (int32_t)a;
+        if (x && x_perm)
+            memcpy((char*)x_perm + (size_t)row * row_bytes,
+                   (const char*)x + (a / (size_t)K) * row_bytes, row_bytes);
+    }
+    free(next);
+    free(list);
+    free(keep);
+    return offsets[E];
+}
+
 /* ---- f_e for one expert over n_rows rows (Section 3.1.1's f_e; SwiGLU) ----
  * x_rows [n_rows,H]; w_gate, w_up [F,H]; w_down [H,F] (all of ONE expert).
  * h [n_rows,F] (may be NULL) and y [n_rows,H] are double. */
