@@ -53,6 +53,9 @@ def parse_args():
     ap.add_argument("--dispatch-backward", action="store_true",
                     help="also time the backward of the dispatcher's two data movements (combine backward, permute "
                          "backward) on the same routing; reported in a separate object, not part of the step")
+    ap.add_argument("--permute-variants", action="store_true",
+                    help="also time moe_permute_variant (drop by score, pad to capacity) on the same routing; "
+                         "workloads with a capacity factor only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the bare-MFMA probe (what this box sustains on zero and on workload-like operands)")
@@ -444,6 +447,35 @@ def main():
             "layer_useful_tflops_fwd_bwd": round(18.0 * R * H * F / ((fms + bms) * 1e-3) / 1e12, 1),
             "note": "weights_transpose re-lays the three expert weight tensors once per optimizer step; "
                     "with several micro-batches per step it is paid once, not per backward"}
+    if args.permute_variants and capacity > 0:
+        s0 = sets[0]
+        vws = torch.empty(moe.permute_variant_workspace_bytes(T, K, E) + 256, dtype=torch.uint8, device="cuda")
+        res = {}
+        for nm, by_score, pad in (("by_position_packed", False, False), ("by_score_packed", True, False),
+                                  ("by_position_padded", False, True), ("by_score_padded", True, True)):
+            rows = E * capacity if pad else r_max
+            xp = torch.empty((rows, H), dtype=tdt, device="cuda")
+            aor = torch.empty((rows,), dtype=torch.int32, device="cuda")
+            def run():
+                moe.permute_variant(s0["x"], s0["idx"], s0["gate"], E, capacity, by_score, pad, xp, s0["counts"],
+                                    s0["offsets"], s0["roa"], aor, vws)
+            for _ in range(args.warmup):
+                run()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                run()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            kept = int(s0["counts"].sum().item())
+            work = (T + (rows if pad else kept)) * H * es + maps      # rows read once; rows written (pad: zeros too)
+            res[nm] = {"ms": round(ms, 4), "kept_rows": kept, "rows_written": rows if pad else kept,
+                       "achieved": round(work / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                       "frac": round(work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        step(s0)      # leave the plain dispatch's maps behind for what follows
+        out["permute_variants"] = res
     if args.dispatch_backward and not fp8:
         # dy plays the gradient of the layer output; the forward's y_perm, maps and gates are reused
         res = {}

@@ -125,6 +125,36 @@ moe_status_t moe_permute(const void* x, const int32_t* topk_idx, int T, int H, i
                          moe_stream_t stream);
 
 /*
+ * Two variants of a2 that capacity-based MoE training uses next to the paper's
+ * default (Eq. 4 fixes the capacity; Section 3.3 drops by position):
+ *
+ *   drop_by_score != 0: an expert with more than `capacity` assignments keeps
+ *     those with the largest scores[t,k] (fp32, finite; compared as floats, -0 =
+ *     +0; equal scores: the lower assignment index wins) instead of the first
+ *     `capacity` in token order.  Typically scores = topk_gate.  Ignored when
+ *     capacity <= 0.
+ *   pad_to_capacity != 0: expert e owns rows [e*capacity, (e+1)*capacity):
+ *     expert_offsets[e] = e*capacity (so the grouped GEMM sees equal groups),
+ *     expert_counts[e] = rows really kept, the rest of each block is zero rows
+ *     with assign_of_row = -1 (zero rows give zero FFN outputs and no assignment
+ *     points at them).  Needs capacity > 0.
+ *
+ * In either variant the kept rows of an expert are in ascending assignment
+ * index.  With both flags 0 the result is moe_permute's.  R_max = rows x_perm and
+ * assign_of_row have room for: at least E*capacity (padded) or
+ * moe_max_rows(T, K, E, capacity) (packed); rows not owned get assign_of_row = -1
+ * and, in the packed layout, are left untouched in x_perm.  scores may be NULL
+ * unless drop_by_score.  workspace: moe_permute_variant_workspace_bytes.
+ */
+size_t moe_permute_variant_workspace_bytes(int T, int K, int E);
+moe_status_t moe_permute_variant(const void* x, const int32_t* topk_idx, const float* scores, int T,
+                                 int H, int E, int K, int capacity, int drop_by_score,
+                                 int pad_to_capacity, moe_dtype_t dt, void* x_perm,
+                                 int32_t* expert_counts, int32_t* expert_offsets,
+                                 int32_t* row_of_assign, int32_t* assign_of_row, int R_max,
+                                 void* workspace, size_t workspace_bytes, moe_stream_t stream);
+
+/*
  * a3. Experts: Section 3.1.2 "Expert Computation"; f_e of Eq. 1 as a bias-free
  * SwiGLU FFN (the paper leaves f_e open):
  *

@@ -78,6 +78,10 @@ def lib() -> C.CDLL:
     L.moe_expert_weights_transpose.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp]
     L.moe_grouped_gemm_swiglu_backward.restype = i
     L.moe_grouped_gemm_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moe_permute_variant_workspace_bytes.restype = sz
+    L.moe_permute_variant_workspace_bytes.argtypes = [i, i, i]
+    L.moe_permute_variant.restype = i
+    L.moe_permute_variant.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, i, vp, sz, vp]
     L.moe_probe_mfma_bf16.restype = i
     L.moe_probe_mfma_bf16.argtypes = [vp, i, i, vp, vp, vp]
     L.moe_expert_gate_up_saving.restype = i
@@ -330,6 +334,25 @@ def permute_backward(dx_perm: torch.Tensor, row_of_assign: torch.Tensor, addend:
     T, H = dx.shape
     _check(lib().moe_permute_backward(_ptr(dx_perm), _ptr(row_of_assign), _ptr(addend), T, H, K, dx_perm.shape[0],
                                       _dt(dx), _ptr(dx), _stream()))
+
+
+def permute_variant_workspace_bytes(T: int, K: int, E: int) -> int:
+    return int(lib().moe_permute_variant_workspace_bytes(T, K, E))
+
+
+def permute_variant(x: Optional[torch.Tensor], topk_idx: torch.Tensor, scores: Optional[torch.Tensor], E: int,
+                    capacity: int, drop_by_score: bool, pad_to_capacity: bool, x_perm: Optional[torch.Tensor],
+                    expert_counts: torch.Tensor, expert_offsets: torch.Tensor, row_of_assign: torch.Tensor,
+                    assign_of_row: torch.Tensor, workspace: torch.Tensor, H: Optional[int] = None,
+                    dtype: Optional[int] = None) -> None:
+    T, K = topk_idx.shape
+    if x is not None:
+        H, dtype = x.shape[1], _dt(x)
+    _check(lib().moe_permute_variant(_ptr(x), _ptr(topk_idx), _ptr(scores), T, H or 8, E, K, capacity,
+                                     int(drop_by_score), int(pad_to_capacity), MOE_BF16 if dtype is None else dtype,
+                                     _ptr(x_perm), _ptr(expert_counts), _ptr(expert_offsets), _ptr(row_of_assign),
+                                     _ptr(assign_of_row), assign_of_row.numel(), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream()))
 
 
 def probe_mfma_bf16(image: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor,

@@ -54,7 +54,6 @@ struct LayerLayout {
     int r_max;
 };
 
-static size_t up256(size_t v) { return (v + 255) & ~size_t(255); }
 
 static LayerLayout layer_layout(int T, int H, int E, int K, int F, int Fs, int capacity, moe_dtype_t dt) {
     LayerLayout L;
@@ -164,6 +163,56 @@ moe_status_t moe_permute(const void* x, const int32_t* topk_idx, int T, int H, i
     launch_permute(x, topk_idx, T, H, E, K, capacity, r_max, dt, x_perm, expert_counts,
                    expert_offsets, row_of_assign, assign_of_row, workspace,
                    static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
+size_t moe_permute_variant_workspace_bytes(int T, int K, int E) {
+    if (T < 0 || K <= 0 || E <= 0) return 0;
+    return permute_variant_workspace_bytes(T, K, E);
+}
+
+moe_status_t moe_permute_variant(const void* x, const int32_t* topk_idx, const float* scores, int T,
+                                 int H, int E, int K, int capacity, int drop_by_score,
+                                 int pad_to_capacity, moe_dtype_t dt, void* x_perm,
+                                 int32_t* expert_counts, int32_t* expert_offsets,
+                                 int32_t* row_of_assign, int32_t* assign_of_row, int R_max,
+                                 void* workspace, size_t workspace_bytes, moe_stream_t stream) {
+    static const char* fn = "moe_permute_variant";
+    if (moe_status_t st = check_dims(fn, T, H, E, K, dt)) return st;
+    if ((x == nullptr) != (x_perm == nullptr))
+        return fail(MOE_ERR_INVALID_ARG, "%s: x and x_perm must both be given or both be NULL", fn);
+    if (pad_to_capacity && capacity <= 0)
+        return fail(MOE_ERR_INVALID_ARG, "%s: the padded layout needs capacity > 0", fn);
+    if (capacity <= 0) drop_by_score = 0;   // nothing is dropped: the rule plays no part
+    const long long need_rows = pad_to_capacity ? (long long)E * capacity : moe_max_rows(T, K, E, capacity);
+    if (need_rows > INT32_MAX) return fail(MOE_ERR_UNSUPPORTED, "%s: E * capacity exceeds the int32 row index", fn);
+    if (R_max < need_rows)
+        return fail(MOE_ERR_INVALID_ARG, "%s: R_max=%d, but this dispatch can produce %lld rows", fn, R_max, need_rows);
+    REQUIRE_PTR(fn, expert_counts);
+    REQUIRE_PTR(fn, expert_offsets);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (T == 0) {
+        launch_fill_i32(expert_counts, E, 0, 0, s);
+        launch_fill_i32(expert_offsets, E + 1, 0, pad_to_capacity ? capacity : 0, s);
+        if (R_max > 0) {
+            REQUIRE_PTR(fn, assign_of_row);
+            launch_fill_i32(assign_of_row, R_max, -1, 0, s);
+            if (pad_to_capacity && x_perm)
+                launch_permute_zero_rows(assign_of_row, x_perm, R_max, H * (dt == MOE_BF16 ? 2 : 4), s);
+        }
+        return check_launch(fn);
+    }
+    REQUIRE_PTR(fn, topk_idx);
+    REQUIRE_PTR(fn, row_of_assign);
+    REQUIRE_PTR(fn, assign_of_row);
+    if (drop_by_score) REQUIRE_PTR(fn, scores);
+    const size_t need = permute_variant_workspace_bytes(T, K, E);
+    if (workspace == nullptr || workspace_bytes < need)
+        return fail(MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                    workspace ? workspace_bytes : (size_t)0);
+    REQUIRE_PTR(fn, workspace);
+    launch_permute_variant(x, topk_idx, scores, T, H, E, K, capacity, drop_by_score, pad_to_capacity, R_max, dt,
+                           x_perm, expert_counts, expert_offsets, row_of_assign, assign_of_row, workspace, s);
     return check_launch(fn);
 }
 

@@ -75,6 +75,17 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
                        const void* w_gate, const void* w_up, const void* w_down, moe_dtype_t dt,
                        void* h, void* y_perm, int variant, int phase, hipStream_t s);
 
+inline size_t up256(size_t v) { return (v + 255) & ~size_t(255); }
+
+size_t permute_variant_workspace_bytes(int T, int K, int E);
+void launch_permute_variant(const void* x, const int32_t* idx, const float* scores, int T, int H, int E, int K,
+                            int capacity, int by_score, int pad, int r_max, moe_dtype_t dt, void* x_perm,
+                            int32_t* counts, int32_t* offsets, int32_t* row_of_assign, int32_t* assign_of_row,
+                            void* ws, hipStream_t s);
+
+// zero the rows r < rows of x_perm with assign_of_row[r] < 0
+void launch_permute_zero_rows(const int32_t* assign_of_row, void* x_perm, int rows, int row_bytes, hipStream_t s);
+
 void launch_fill_i32(int32_t* p, int n, int32_t v0, int32_t step, hipStream_t s);
 
 // ---- pieces of the expert FFN's backward (bf16) ----

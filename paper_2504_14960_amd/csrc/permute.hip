@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __rest
 
 __global__ __launch_bounds__(256) void permute_map_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ chunk_hist, int A, int E,
-    int capacity, int r_max, int nchunks, int32_t* __restrict__ counts,
+    int capacity, int pad, int r_max, int nchunks, int32_t* __restrict__ counts,
     int32_t* __restrict__ offsets, int32_t* __restrict__ row_of_assign,
     int32_t* __restrict__ assign_of_row) {
     __shared__ int tot[kMaxExperts];
@@ -87,9 +87,11 @@ __global__ __launch_bounds__(256) void permute_map_kernel(
         cur ^= 1;
         __syncthreads();
     }
-    const int incl = scan[cur][tid];
+    // padded layout: every expert owns a block of `capacity` rows, whatever it keeps
+    const int incl = pad ? (tid + 1) * capacity : scan[cur][tid];
     if (tid < E) off[tid + 1] = incl;
     if (tid == 0) off[0] = 0;
+    if (pad) tot[tid] = cnt;   // kept rows per expert, for the marking of the unused rows below
     if (chunk == 0) {
         if (tid < E) {
             counts[tid] = cnt;
@@ -148,9 +150,163 @@ __global__ __launch_bounds__(256) void permute_map_kernel(
             if (row >= 0) assign_of_row[row] = a;
         }
     }
-    // rows past the kept total are marked unused
-    const int R = off[E];
-    for (int r = R + chunk * 256 + tid; r < r_max; r += nchunks * 256) assign_of_row[r] = -1;
+    // rows past the kept total are marked unused; in the padded layout also the tail of every block
+    if (pad) {
+        __syncthreads();   // tot[] now holds the kept counts
+        for (int r = chunk * 256 + tid; r < r_max; r += nchunks * 256) {
+            const int e = r / capacity;
+            if (e >= E || r - e * capacity >= tot[e]) assign_of_row[r] = -1;
+        }
+    } else {
+        const int R = off[E];
+        for (int r = R + chunk * 256 + tid; r < r_max; r += nchunks * 256) assign_of_row[r] = -1;
+    }
+}
+
+// ---- drop by score ----
+// Order-preserving 32-bit key of a finite float (larger float <=> larger key; -0 = +0).
+__device__ __forceinline__ uint32_t score_key(float s) {
+    uint32_t b = __float_as_uint(s);
+    if (s == 0.f) b = 0u;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+constexpr int kSelThreads = 1024;   // threads of permute_select_kernel
+
+// exclusive prefix of a flag over the threads of the workgroup and its total; `wsum` is LDS scratch, one int per wave
+__device__ __forceinline__ int block_rank(bool flag, int* wsum, int& total) {
+    constexpr int NWAVE = kSelThreads / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t m = __ballot(flag);
+    const uint64_t lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    __syncthreads();   // the previous use of wsum is over
+    if (lane == 0) wsum[wave] = __popcll(m);
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < NWAVE; ++w) {
+        const int c = wsum[w];
+        before += (w < wave) ? c : 0;
+        all += c;
+    }
+    total = all;
+    return before + __popcll(m & lt);
+}
+
+// One workgroup per expert.  seg_off / seg_aor: the dropless grouping (expert e's assignments in
+// ascending index at seg_aor[seg_off[e] .. seg_off[e+1])).  An expert with more than `capacity`
+// assignments keeps those with the largest scores (ties: lower assignment index): the capacity-th
+// largest 32-bit key is found by a 4-pass radix selection over the expert's keys, then one ordered
+// pass assigns rows to the kept assignments in ascending assignment index.  row_of_assign holds -1
+// for assignments without a valid expert on entry (written by the dropless grouping).
+__global__ __launch_bounds__(kSelThreads) void permute_select_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ seg_off, const int32_t* __restrict__ seg_aor,
+    uint32_t* __restrict__ keys, int E, int capacity, int pad, int r_max, int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ row_of_assign, int32_t* __restrict__ assign_of_row) {
+    __shared__ int scan[2][kMaxExperts];
+    __shared__ int hist[256];
+    __shared__ int wsum[kSelThreads / 64];
+    __shared__ uint32_t sel[2];   // decided key prefix, keys still to take at this prefix
+    const int tid = threadIdx.x, e = blockIdx.x;
+    // rows kept by every expert, and this expert's first row (scan by the first kMaxExperts threads)
+    const bool scanner = tid < kMaxExperts;
+    const int n_mine = (tid < E) ? seg_off[tid + 1] - seg_off[tid] : 0;
+    const int cnt = n_mine > capacity ? capacity : n_mine;
+    if (scanner) scan[0][tid] = cnt;
+    __syncthreads();
+    int cur = 0;
+    for (int d = 1; d < kMaxExperts; d <<= 1) {
+        if (scanner) scan[cur ^ 1][tid] = scan[cur][tid] + ((tid >= d) ? scan[cur][tid - d] : 0);
+        cur ^= 1;
+        __syncthreads();
+    }
+    const int lo = seg_off[e], n = seg_off[e + 1] - lo;
+    const int kept = n > capacity ? capacity : n;
+    const int base = pad ? e * capacity : (e ? scan[cur][e - 1] : 0);
+    const int R = pad ? E * capacity : scan[cur][E - 1];
+    if (tid == 0) {
+        counts[e] = kept;
+        offsets[e] = base;
+        if (e == E - 1) offsets[E] = R;
+    }
+    const bool all = n <= capacity;
+    uint32_t thr = 0;
+    int need_eq = 0;
+    if (!all) {   // uniform over the workgroup
+        if (tid == 0) {
+            sel[0] = 0u;
+            sel[1] = (uint32_t)capacity;
+        }
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            const uint32_t prefix = sel[0];
+#pragma unroll 4
+            for (int i = tid; i < n; i += kSelThreads) {
+                uint32_t key;
+                if (pass == 0) {
+                    key = score_key(scores[seg_aor[lo + i]]);
+                    keys[lo + i] = key;
+                } else {
+                    key = keys[lo + i];
+                }
+                // 64-bit shift: the first pass compares nothing
+                if (((uint64_t)(key ^ prefix) >> (shift + 8)) == 0) atomicAdd(&hist[(key >> shift) & 255u], 1);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int remaining = (int)sel[1], d = 255;
+                while (d > 0 && hist[d] < remaining) {   // the digit that holds the `remaining`-th largest key
+                    remaining -= hist[d];
+                    --d;
+                }
+                sel[0] = prefix | ((uint32_t)d << shift);
+                sel[1] = (uint32_t)remaining;
+            }
+            __syncthreads();
+        }
+        thr = sel[0];
+        need_eq = (int)sel[1];   // keys equal to thr that are still kept: the first need_eq in index order
+    }
+    int run_eq = 0, run_kept = 0;
+    for (int c0 = 0; c0 < n; c0 += kSelThreads) {
+        const int i = c0 + tid;
+        const bool valid = i < n;
+        const int a = valid ? seg_aor[lo + i] : -1;
+        const uint32_t key = (valid && !all) ? keys[lo + i] : 0u;
+        const bool gt = valid && (all || key > thr);
+        const bool eq = valid && !all && key == thr;
+        int tot_eq, tot_keep;
+        const int eq_rank = run_eq + block_rank(eq, wsum, tot_eq);
+        const bool keep = gt || (eq && eq_rank < need_eq);
+        const int k_rank = run_kept + block_rank(keep, wsum, tot_keep);
+        if (valid) {
+            int row = keep ? base + k_rank : -1;
+            if (row >= r_max) row = -1;   // cannot happen for a consistent r_max; never an address
+            row_of_assign[a] = row;
+            if (row >= 0) assign_of_row[row] = a;
+        }
+        run_eq += tot_eq;
+        run_kept += tot_keep;
+    }
+    // unused rows
+    if (pad) {
+        for (int r = base + kept + tid; r < base + capacity && r < r_max; r += kSelThreads) assign_of_row[r] = -1;
+    }
+    for (int r = R + e * kSelThreads + tid; r < r_max; r += E * kSelThreads) assign_of_row[r] = -1;
+}
+
+// Zero the rows that no assignment owns (padded layout).  One wave per row.
+__global__ __launch_bounds__(256) void permute_zero_rows_kernel(const int32_t* __restrict__ assign_of_row,
+                                                                uint8_t* __restrict__ x_perm, int rows,
+                                                                int row_bytes) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int r = blockIdx.x * 4 + wave; r < rows; r += gridDim.x * 4) {
+        if (assign_of_row[r] >= 0) continue;
+        uint8_t* dst = x_perm + (size_t)r * row_bytes;
+        for (int o = lane * 16; o < row_bytes; o += 1024) *reinterpret_cast<u32x4*>(dst + o) = u32x4{0u, 0u, 0u, 0u};
+    }
 }
 
 // One wave per token.  row_bytes is a multiple of 16.
@@ -268,7 +424,7 @@ void launch_permute(const void* x, const int32_t* idx, int T, int H, int E, int 
     int32_t* chunk_hist = static_cast<int32_t*>(ws);
     hipLaunchKernelGGL(permute_hist_kernel, dim3(nchunks), dim3(256), 0, s, idx, A, E, chunk_hist);
     hipLaunchKernelGGL(permute_map_kernel, dim3(nchunks), dim3(256), 0, s, idx, chunk_hist, A, E,
-                       capacity, r_max, nchunks, counts, offsets, row_of_assign, assign_of_row);
+                       capacity, 0, r_max, nchunks, counts, offsets, row_of_assign, assign_of_row);
     if (x != nullptr && x_perm != nullptr) {
         const int row_bytes = H * (dt == MOE_BF16 ? 2 : 4);
         int grid = (T + 3) / 4;
@@ -277,6 +433,60 @@ void launch_permute(const void* x, const int32_t* idx, int T, int H, int E, int 
                            static_cast<const uint8_t*>(x), row_of_assign,
                            static_cast<uint8_t*>(x_perm), T, K, row_bytes, r_max);
     }
+}
+
+// Layout of the variant's workspace: chunk histograms, then the dropless grouping (offsets, rows) and the keys
+size_t permute_variant_workspace_bytes(int T, int K, int E) {
+    const size_t A = (size_t)T * K;
+    return up256(permute_workspace_bytes(T, K, E)) + up256((size_t)(E + 1) * 4) + up256((size_t)E * 4) +
+           up256((A + 1) * 4) + up256((A + 1) * 4);
+}
+
+// Dispatch with the drop rule (by position / by score) and the layout (packed / padded to capacity) chosen.
+// capacity > 0 whenever by_score or pad is set.
+void launch_permute_variant(const void* x, const int32_t* idx, const float* scores, int T, int H, int E, int K,
+                            int capacity, int by_score, int pad, int r_max, moe_dtype_t dt, void* x_perm,
+                            int32_t* counts, int32_t* offsets, int32_t* row_of_assign, int32_t* assign_of_row,
+                            void* ws, hipStream_t s) {
+    const int A = T * K;
+    const int nchunks = (A + kChunk - 1) / kChunk;
+    uint8_t* w = static_cast<uint8_t*>(ws);
+    int32_t* chunk_hist = reinterpret_cast<int32_t*>(w);
+    w += up256(permute_workspace_bytes(T, K, E));
+    int32_t* seg_off = reinterpret_cast<int32_t*>(w);
+    w += up256((size_t)(E + 1) * 4);
+    int32_t* seg_cnt = reinterpret_cast<int32_t*>(w);
+    w += up256((size_t)E * 4);
+    int32_t* seg_aor = reinterpret_cast<int32_t*>(w);
+    w += up256(((size_t)A + 1) * 4);
+    uint32_t* keys = reinterpret_cast<uint32_t*>(w);
+    hipLaunchKernelGGL(permute_hist_kernel, dim3(nchunks), dim3(256), 0, s, idx, A, E, chunk_hist);
+    if (by_score) {
+        // dropless grouping first (row_of_assign serves as its scratch map), then the selection per expert
+        hipLaunchKernelGGL(permute_map_kernel, dim3(nchunks), dim3(256), 0, s, idx, chunk_hist, A, E, 0, 0, A,
+                           nchunks, seg_cnt, seg_off, row_of_assign, seg_aor);
+        hipLaunchKernelGGL(permute_select_kernel, dim3(E), dim3(kSelThreads), 0, s, scores, seg_off, seg_aor, keys, E,
+                           capacity, pad, r_max, counts, offsets, row_of_assign, assign_of_row);
+    } else {
+        hipLaunchKernelGGL(permute_map_kernel, dim3(nchunks), dim3(256), 0, s, idx, chunk_hist, A, E, capacity,
+                           pad, r_max, nchunks, counts, offsets, row_of_assign, assign_of_row);
+    }
+    if (x != nullptr && x_perm != nullptr) {
+        const int row_bytes = H * (dt == MOE_BF16 ? 2 : 4);
+        int grid = (T + 3) / 4;
+        if (grid > 256 * 16) grid = 256 * 16;
+        hipLaunchKernelGGL(permute_copy_kernel, dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(x),
+                           row_of_assign, static_cast<uint8_t*>(x_perm), T, K, row_bytes, r_max);
+        if (pad) launch_permute_zero_rows(assign_of_row, x_perm, r_max, row_bytes, s);
+    }
+}
+
+void launch_permute_zero_rows(const int32_t* assign_of_row, void* x_perm, int rows, int row_bytes, hipStream_t s) {
+    if (rows <= 0) return;
+    int grid = (rows + 3) / 4;
+    if (grid > 256 * 16) grid = 256 * 16;
+    hipLaunchKernelGGL(permute_zero_rows_kernel, dim3(grid), dim3(256), 0, s, assign_of_row,
+                       static_cast<uint8_t*>(x_perm), rows, row_bytes);
 }
 
 void launch_permute_fp8(const void* x, const int32_t* idx, int T, int H, int E, int K, int capacity, int r_max,
