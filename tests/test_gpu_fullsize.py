@@ -300,3 +300,40 @@ def test_full_size_ffn_backward(name):
         close(to_host(dwd[e][:, f_dev].contiguous()), rd[0], f"dw_down expert {e} ({name})")
     for e in np.nonzero(perm.counts == 0)[0]:
         assert (values(to_host(dwd[int(e)])) == 0).all()
+
+
+@pytest.mark.parametrize("name", ["tokendrop", "mixtral8x22b_g8t8"])
+@pytest.mark.parametrize("by_score,pad", [(True, False), (True, True), (False, True)])
+def test_full_size_permute_variants(name, by_score, pad):
+    """The dispatch variants at full size, as bench.py --permute-variants launches them: maps, counts and offsets
+    in full (bit-exact); the rows of x_perm in full too (a row copy is checked by indexing the source)."""
+    import torch
+    import paper_2504_14960_amd as moe
+    cfg = get_config(name)
+    T, H, E, K = cfg.T, cfg.H, cfg.E, cfg.K
+    inp = make_layer_inputs(cfg, ["x", "w_router"])
+    capacity = capacity_rows(cfg)
+    l32 = oracle.router_logits(inp["x"], inp["w_router"], inp.bias).astype(np.float32)
+    idx, gate = oracle.topk_gates(l32, K, cfg.renormalize)
+    scores = gate.astype(np.float32)
+    want = oracle.permute_variant(None, idx, scores, E, capacity, by_score, pad)
+    r_max = E * capacity if pad else moe.max_rows(T, K, E, capacity)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_x = to_dev(inp["x"])
+    x_perm = torch.full((r_max, H), 5.0, dtype=d_x.dtype, device="cuda")
+    counts, offsets = torch.empty((E,), **i32), torch.empty((E + 1,), **i32)
+    roa, aor = torch.empty((T * K,), **i32), torch.empty((r_max,), **i32)
+    ws = torch.empty(moe.permute_variant_workspace_bytes(T, K, E) + 256, dtype=torch.uint8, device="cuda")
+    moe.permute_variant(d_x, to_dev(idx), to_dev(scores), E, capacity, by_score, pad, x_perm, counts, offsets, roa, aor, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host(counts), want.counts)
+    np.testing.assert_array_equal(to_host(offsets), want.offsets)
+    np.testing.assert_array_equal(to_host(roa), want.row_of_assign)
+    np.testing.assert_array_equal(to_host(aor), want.assign_of_row[:r_max])
+    # every owned row is a copy of its token's row; unowned rows are zero (padded) or untouched (packed)
+    d_aor = aor.to(torch.int64)
+    owned = d_aor >= 0
+    src = d_x[(d_aor.clamp(min=0) // K)]
+    assert torch.equal(x_perm[owned].view(torch.int16), src[owned].view(torch.int16))
+    rest = x_perm[~owned].float()
+    assert rest.numel() == 0 or bool((rest == (0.0 if pad else 5.0)).all())
