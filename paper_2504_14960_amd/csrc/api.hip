@@ -478,14 +478,16 @@ moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h,
             ok = launch_grouped_nt(x_perm, expert_offsets, R_max, E, F, H, w_gate, ws + L.g, s);
             ok = ok && launch_grouped_nt(x_perm, expert_offsets, R_max, E, F, H, w_up, ws + L.u, s);
         }
-        ok = ok && launch_grouped_nt(dy_perm, expert_offsets, R_max, E, F, H, wd_t, ws + L.dh, s);
+        if (gu) {
+            // dh is formed in the GEMM's accumulators and turned into dg | du in its epilogue
+            ok = launch_grouped_nt_swiglu_bwd(dy_perm, expert_offsets, R_max, E, F, H, wd_t, gu, ws + L.dgdu, s);
+        } else {
+            ok = ok && launch_grouped_nt(dy_perm, expert_offsets, R_max, E, F, H, wd_t, ws + L.dh, s);
+            if (ok)
+                launch_swiglu_backward(ws + L.dh, ws + L.g, ws + L.u, (size_t)F, expert_offsets + E, R_max, F,
+                                       ws + L.dgdu, s);
+        }
         if (!ok) return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
-        if (gu)
-            launch_swiglu_backward(ws + L.dh, gu, static_cast<const uint8_t*>(gu) + (size_t)F * 2, (size_t)2 * F,
-                                   expert_offsets + E, R_max, F, ws + L.dgdu, s);
-        else
-            launch_swiglu_backward(ws + L.dh, ws + L.g, ws + L.u, (size_t)F, expert_offsets + E, R_max, F,
-                                   ws + L.dgdu, s);
         if (!launch_grouped_nt(ws + L.dgdu, expert_offsets, R_max, E, H, 2 * F, wgu_t, dx_perm, s))
             return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
         // operands of the weight gradients, transposed with every expert's rows as a zero-padded column segment

@@ -100,6 +100,9 @@ void launch_ragged_transpose(const void* src, const int32_t* offsets, int E, int
 // out [rows, 2F] = dg | du from dh [rows, F] and g, u (rows ld_gu elements apart); rows = *n_rows (device)
 void launch_swiglu_backward(const void* dh, const void* g, const void* u, size_t ld_gu, const int32_t* n_rows,
                             int r_max, int F, void* out, hipStream_t s);
+// dh = A . B[e]^T fused with the SwiGLU derivative: writes dg | du [rows, 2N] from the saved gu [rows, 2N]
+bool launch_grouped_nt_swiglu_bwd(const void* A, const int32_t* offsets, int r_max, int E, int N, int K,
+                                  const void* B, const void* gu, void* dgdu, hipStream_t s);
 // the forward's gate/up GEMM that also stores the pre-activations g | u to gu [rows, 2F]; false if not covered
 bool launch_gate_up_saving(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                            const void* w_gate, const void* w_up, void* h, void* gu, hipStream_t s);

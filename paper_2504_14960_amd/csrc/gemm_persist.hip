@@ -61,7 +61,7 @@ template <int FM, int FN, int WM, int MODE, bool ACC_IN_AGPR>
 __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_row0, int t_rows, int t_n0,
                                                   bf16_t* __restrict__ C, bf16_t* __restrict__ GU, int N, int wm,
                                                   int wn, int lane, uint8_t* stage) {
-    constexpr bool SWIGLU = MODE != 0;
+    constexpr bool SWIGLU = MODE == 1 || MODE == 2;
     constexpr int FO = SWIGLU ? FN / 2 : FN;
     constexpr int W = FO * 64;        // bytes per staged row
     constexpr int GPR = W / 16;       // granules per row
@@ -137,14 +137,58 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_r
             }
         }
         __builtin_amdgcn_sched_barrier(0);
+        if (MODE == 3) {
+            // the saved pre-activations of this row block first (their addresses do not depend on the staging)
+            u32x4 gv[32 / RPI], uv[32 / RPI];
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int row = it * RPI + rl;
-            const int xr = (row / RP256) & (GPR - 1);
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * W + ((gl ^ xr) << 4));
-            const int grow = wm * WM + i * 32 + row;
-            if (grow < t_rows && col < N)
-                *reinterpret_cast<u32x4*>(C + (size_t)(t_row0 + grow) * N + col) = v;
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int grow = wm * WM + i * 32 + it * RPI + rl;
+                gv[it] = u32x4{0u, 0u, 0u, 0u};
+                uv[it] = u32x4{0u, 0u, 0u, 0u};
+                if (grow < t_rows && col < N) {
+                    const bf16_t* src = GU + (size_t)(t_row0 + grow) * (2 * N) + col;
+                    gv[it] = *reinterpret_cast<const u32x4*>(src);
+                    uv[it] = *reinterpret_cast<const u32x4*>(src + N);
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int row = it * RPI + rl;
+                const int xr = (row / RP256) & (GPR - 1);
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * W + ((gl ^ xr) << 4));
+                const int grow = wm * WM + i * 32 + row;
+                u32x4 og, ou;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float dgv[2], duv[2];
+#pragma unroll
+                    for (int hlf = 0; hlf < 2; ++hlf) {
+                        const float dh = __uint_as_float(hlf ? (v[j] & 0xffff0000u) : (v[j] << 16));
+                        const float g = __uint_as_float(hlf ? (gv[it][j] & 0xffff0000u) : (gv[it][j] << 16));
+                        const float up = __uint_as_float(hlf ? (uv[it][j] & 0xffff0000u) : (uv[it][j] << 16));
+                        const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-g));
+                        duv[hlf] = dh * g * sg;
+                        dgv[hlf] = dh * up * sg * (1.f + g * (1.f - sg));
+                    }
+                    og[j] = pack2_bf16(dgv[0], dgv[1]);
+                    ou[j] = pack2_bf16(duv[0], duv[1]);
+                }
+                if (grow < t_rows && col < N) {
+                    bf16_t* dst = C + (size_t)(t_row0 + grow) * (2 * N) + col;
+                    *reinterpret_cast<u32x4*>(dst) = og;
+                    *reinterpret_cast<u32x4*>(dst + N) = ou;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int row = it * RPI + rl;
+                const int xr = (row / RP256) & (GPR - 1);
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stage + row * W + ((gl ^ xr) << 4));
+                const int grow = wm * WM + i * 32 + row;
+                if (grow < t_rows && col < N)
+                    *reinterpret_cast<u32x4*>(C + (size_t)(t_row0 + grow) * N + col) = v;
+            }
         }
     }
 }
@@ -154,7 +198,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, bf16_t* __restrict__ GU,
     int ntn) {
-    constexpr bool SWIGLU = MODE != 0;
+    constexpr bool SWIGLU = MODE == 1 || MODE == 2;
     constexpr int BK = 64;
     constexpr int NW = WGM * WGN;
     constexpr int NT = NW * 64;
@@ -439,7 +483,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
 template <int BM, int BN, int WGM, int WGN, int MODE>
 void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B0,
                     const void* B1, void* C, void* GU, hipStream_t s) {
-    constexpr int OUTN = MODE != 0 ? BN / 2 : BN;
+    constexpr int OUTN = (MODE == 1 || MODE == 2) ? BN / 2 : BN;
     constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
     const int ntn = (N + OUTN - 1) / OUTN;
     auto kern = gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE>;
@@ -474,6 +518,14 @@ bool launch_grouped_nt(const void* A, const int32_t* offsets, int r_max, int E, 
                        void* C, hipStream_t s) {
     if (K < 128 || K % 64 || N % 8) return false;
     launch_persist<256, 256, 2, 4, 0>(A, offsets, r_max, E, N, K, B, nullptr, C, nullptr, s);
+    return true;
+}
+
+// dg | du [rows, 2N] from dh = A . B[e]^T (never stored) and the saved pre-activations gu [rows, 2N]
+bool launch_grouped_nt_swiglu_bwd(const void* A, const int32_t* offsets, int r_max, int E, int N, int K,
+                                  const void* B, const void* gu, void* dgdu, hipStream_t s) {
+    if (K < 128 || K % 64 || N % 8) return false;
+    launch_persist<256, 256, 2, 4, 3>(A, offsets, r_max, E, N, K, B, nullptr, dgdu, const_cast<void*>(gu), s);
     return true;
 }
 
