@@ -498,9 +498,11 @@ moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h,
     }
     // with R_max == 0 every segment is empty and the three launches below write zeros without reading
     const int ld = R_max > 0 ? L.rp_max : 64;
-    launch_wgrad_gemm(ws + L.dy_t, ws + L.h_t, expert_offsets, E, H, F, ld, dw_down, s);
-    launch_wgrad_gemm(ws + L.dgdu_t, ws + L.x_t, expert_offsets, E, F, H, ld, dw_gate, s);
-    launch_wgrad_gemm(ws + L.dgdu_t + (size_t)F * ld * 2, ws + L.x_t, expert_offsets, E, F, H, ld, dw_up, s);
+    // "gemm_variant" 30 / 31 select the one-workgroup-per-tile kernel, anything else the persistent one
+    auto wgrad = (g_gemm_variant == 30 || g_gemm_variant == 31) ? launch_pipe3_wgrad : launch_persist_wgrad;
+    wgrad(ws + L.dy_t, ws + L.h_t, expert_offsets, E, H, F, ld, dw_down, s);
+    wgrad(ws + L.dgdu_t, ws + L.x_t, expert_offsets, E, F, H, ld, dw_gate, s);
+    wgrad(ws + L.dgdu_t + (size_t)F * ld * 2, ws + L.x_t, expert_offsets, E, F, H, ld, dw_up, s);
     return check_launch(fn);
 }
 

@@ -107,8 +107,11 @@ bool launch_grouped_nt_swiglu_bwd(const void* A, const int32_t* offsets, int r_m
 bool launch_gate_up_saving(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                            const void* w_gate, const void* w_up, void* h, void* gu, hipStream_t s);
 // dw [E, M, N] = per expert a_t[:, seg_e] . b_t[:, seg_e]^T over the expert's padded column segment
-void launch_wgrad_gemm(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
-                       void* dw, hipStream_t s);
+// persistent: one workgroup per compute unit; pipe3: one workgroup per output tile
+void launch_persist_wgrad(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
+                          void* dw, hipStream_t s);
+void launch_pipe3_wgrad(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
+                        void* dw, hipStream_t s);
 
 // measurement probe: the bare bf16 MFMA + LDS-fragment loop over a 64 KiB operand image
 void launch_probe_mfma_bf16(const void* image, int iters, int workgroups, float* sink, unsigned long long* ticks,

@@ -29,6 +29,7 @@ struct PTile {
     uint32_t a_lim;     // byte offset (from a) of the last valid activation row
     uint32_t b_lim;     // byte offset (from b0 / b1) of the last valid weight row
     int row0, rows, n0;
+    int kt;             // k-tiles of this output tile (weight-gradient form; 0 = the launch's common count)
     bool valid;
 };
 
@@ -78,7 +79,7 @@ struct TileSched {
                                          size_t row_bytes, int outn) const {
         constexpr int MG = 8;
         PTile t;
-        t.a = A; t.b0 = B0; t.b1 = B1; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0;
+        t.a = A; t.b0 = B0; t.b1 = B1; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0; t.kt = 0;
         const int j = wgx + i * nwx;
         const int L = xcd * per + j;
         t.valid = (j < per) && (L < total);
@@ -129,6 +130,106 @@ struct TileSched {
         t.b1 = uni(B1 + brow);
         t.a_lim = uni((uint32_t)(t.rows - 1) * (uint32_t)k2);
         t.b_lim = uni((uint32_t)(min(outn, N - t.n0) - 1) * (uint32_t)k2);
+        return t;
+    }
+};
+
+// Schedule of the weight-gradient form: C [E, M, N], for expert e the product of
+// A_t[:, seg_e] and B_t[:, seg_e]^T over the expert's zero-padded column segment
+// (padded length = 0 for an expert without rows, else max(128, n rounded up to
+// 64)).  Every non-empty expert has the same mt x nt output tiles; what differs
+// from tile to tile is the number of k-tiles, so the XCD shares are cut by work,
+// not by tile count: every XCD takes the same eighth of EVERY expert's tiles (a
+// contiguous block of the expert's tile order, so the tiles an XCD runs at once
+// still share panels in its L2), and its workgroups walk that list round-robin.
+// Lane l describes experts 4l..4l+3.
+template <int BM, int BN>
+struct WgradSched {
+    int seg[4], len[4], pex[4], pend;   // segment start / padded length (elements), prefix of non-empty experts
+    int mt, nt, tpe, nwx, wgx, part0, part_n, total;   // part0/part_n: this XCD's slice of an expert's tiles
+
+    __device__ __forceinline__ void init(const int32_t* __restrict__ offsets, int E, int M, int N, int lane) {
+        int s_len = 0, s_cnt = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = lane * 4 + j;
+            int n = 0;
+            if (e < E) n = offsets[e + 1] - offsets[e];
+            len[j] = n <= 0 ? 0 : max(128, (n + 63) & ~63);
+            s_len += len[j];
+            s_cnt += len[j] > 0;
+        }
+        int incl_len = s_len, incl_cnt = s_cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int ol = __shfl_up(incl_len, d, 64), oc = __shfl_up(incl_cnt, d, 64);
+            if (lane >= d) {
+                incl_len += ol;
+                incl_cnt += oc;
+            }
+        }
+        seg[0] = incl_len - s_len;
+        pex[0] = incl_cnt - s_cnt;
+#pragma unroll
+        for (int j = 1; j < 4; ++j) {
+            seg[j] = seg[j - 1] + len[j - 1];
+            pex[j] = pex[j - 1] + (len[j - 1] > 0);
+        }
+        pend = incl_cnt;
+        mt = (M + BM - 1) / BM;
+        nt = (N + BN - 1) / BN;
+        tpe = mt * nt;
+        const int xcd = blockIdx.x & 7;
+        part0 = (int)((long long)xcd * tpe / 8);
+        part_n = (int)((long long)(xcd + 1) * tpe / 8) - part0;
+        total = __builtin_amdgcn_readlane(incl_cnt, 63) * part_n;   // tiles of this XCD
+        wgx = blockIdx.x >> 3;
+        nwx = (gridDim.x + 7 - xcd) >> 3;
+    }
+
+    // the i-th tile of this workgroup; ld = elements per row of A_t and B_t
+    __device__ __forceinline__ PTile get(int i, const uint8_t* A, const uint8_t* B, int M, int N, int ld) const {
+        constexpr int MG = 8;
+        PTile t;
+        t.a = A; t.b0 = B; t.b1 = B; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0; t.kt = 0;
+        const int j = wgx + i * nwx;
+        t.valid = j < total;
+        if (!t.valid) return t;
+        const int qe = j / part_n;   // index among the non-empty experts (part_n > 0 since total > 0)
+        int hit = -1, my_seg = 0, my_len = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (len[q] > 0 && pex[q] == qe) {
+                hit = q; my_seg = seg[q]; my_len = len[q];
+            }
+        const uint64_t bal = __ballot(hit >= 0);  // exactly one lane holds the qe-th non-empty expert
+        const int src = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)bal) - 1);
+        const int e = 4 * src + __builtin_amdgcn_readlane(hit, src);
+        const int seg_e = __builtin_amdgcn_readlane(my_seg, src);
+        const int len_e = __builtin_amdgcn_readlane(my_len, src);
+        // inside an expert: groups of MG M-tiles, ordered (M-group, N, M-in-group)
+        const int Le = part0 + j - qe * part_n;
+        const int full = (mt / MG) * MG * nt;
+        int m, n;
+        if (Le < full) {
+            const int g = Le / (MG * nt), rem = Le - g * MG * nt;
+            n = rem / MG;
+            m = g * MG + rem - n * MG;
+        } else {
+            const int tail = mt % MG, rem = Le - full;   // tail > 0 here
+            n = rem / tail;
+            m = (mt / MG) * MG + rem - n * tail;
+        }
+        const size_t k2 = (size_t)ld * 2;
+        t.rows = uni(min(BM, M - m * BM));
+        t.row0 = uni(e * M + m * BM);
+        t.n0 = uni(n * BN);
+        t.kt = uni(len_e / 64);
+        t.a = uni(A + (size_t)(m * BM) * k2 + (size_t)seg_e * 2);
+        t.b0 = uni(B + (size_t)(n * BN) * k2 + (size_t)seg_e * 2);
+        t.b1 = t.b0;
+        t.a_lim = uni((uint32_t)(t.rows - 1) * (uint32_t)k2);
+        t.b_lim = uni((uint32_t)(min(BN, N - t.n0) - 1) * (uint32_t)k2);
         return t;
     }
 };

@@ -19,6 +19,8 @@
 //
 // The workgroups never wait for one another, so any number of them may be
 // resident; the launcher asks for one per compute unit.
+#include <type_traits>
+
 #include "gemm_persist.h"
 
 namespace moe {
@@ -193,11 +195,17 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_r
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE>
+// GROUPK (MODE 0 only): the weight-gradient form C [E, M, N]; A and B0 are the
+// transposed operands [M, K] and [N, K] with K = elements per row, every expert
+// contracting over its own zero-padded column segment (see WgradSched); `ntn`
+// carries M.  Experts without rows get no tiles here (their gradient is zeroed
+// by wgrad_zero_empty_kernel).
+template <int BM, int BN, int WGM, int WGN, int MODE, bool GROUPK = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, bf16_t* __restrict__ GU,
     int ntn) {
+    static_assert(!GROUPK || MODE == 0, "the weight-gradient form has a plain epilogue");
     constexpr bool SWIGLU = MODE == 1 || MODE == 2;
     constexpr int BK = 64;
     constexpr int NW = WGM * WGN;
@@ -244,24 +252,36 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const uint8_t* const B0b = reinterpret_cast<const uint8_t*>(B0);
     const uint8_t* const B1b = SWIGLU ? reinterpret_cast<const uint8_t*>(B1) : B0b;
 
-    TileSched<BM> sched;
-    sched.init(offsets, E, ntn, lane);
+    typename std::conditional<GROUPK, WgradSched<BM, BN>, TileSched<BM>>::type sched;
+    if constexpr (GROUPK)
+        sched.init(offsets, E, ntn, N, lane);
+    else
+        sched.init(offsets, E, ntn, lane);
+    auto get_tile = [&](int i) -> PTile {
+        if constexpr (GROUPK)
+            return sched.get(i, Ab, B0b, ntn, N, K);
+        else
+            return sched.get(i, Ab, B0b, B1b, N, (size_t)K * 2, OUTN);
+    };
     // current and next tile of this workgroup, as plain wave-uniform scalars
     int ti = 0;
     const uint8_t *c_a, *c_b0, *c_b1, *n_a, *n_b0, *n_b1;
     uint32_t c_alim, c_blim, n_alim, n_blim;
     int c_row0, c_rows, c_n0, n_row0, n_rows, n_n0;
+    int c_kt = K / BK, n_kt = K / BK;   // k-tiles per output tile: per tile in the weight-gradient form
     bool n_valid;
     {
-        const PTile t = sched.get(0, Ab, B0b, B1b, N, (size_t)K * 2, OUTN);
+        const PTile t = get_tile(0);
         if (!t.valid) return;
         c_a = t.a; c_b0 = t.b0; c_b1 = t.b1; c_alim = t.a_lim; c_blim = t.b_lim;
         c_row0 = t.row0; c_rows = t.rows; c_n0 = t.n0;
+        if (GROUPK) c_kt = t.kt;
     }
     auto fetch_next_tile = [&](int i) {
-        const PTile t = sched.get(i, Ab, B0b, B1b, N, (size_t)K * 2, OUTN);
+        const PTile t = get_tile(i);
         n_a = t.a; n_b0 = t.b0; n_b1 = t.b1; n_alim = t.a_lim; n_blim = t.b_lim;
         n_row0 = t.row0; n_rows = t.rows; n_n0 = t.n0; n_valid = t.valid;
+        if (GROUPK) n_kt = t.kt;
     };
     fetch_next_tile(1);
 
@@ -296,8 +316,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         const uint8_t* b1;
         uint32_t a_lim, b_lim;
     };
-    const int KT = K / BK;
+    // every tile has at least two k-tiles, so k-tile KT + 1 of the stream is the next tile's second
     auto src = [&](int kk) -> Src {
+        const int KT = c_kt;
         const bool in_cur = kk < KT;
         const bool use_cur = in_cur || !n_valid;  // past the last tile: its last k-tile again, never used
         const int k = in_cur ? kk : (n_valid ? kk - KT : KT - 1);
@@ -413,7 +434,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
 #ifdef MOE_PIPE_TIMING
         const unsigned long long tk_l0 = __builtin_amdgcn_s_memtime();
 #endif
-        for (int kt = 0; kt < KT; ++kt) {
+        for (int kt = 0; kt < c_kt; ++kt) {
             const Src s1 = src(kt + 1), s2 = src(kt + 2);
             const uint8_t* ca = a_region + l0;
             const uint8_t* cb = b_region + e0;
@@ -451,6 +472,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         if (!n_valid) break;
         c_a = n_a; c_b0 = n_b0; c_b1 = n_b1; c_alim = n_alim; c_blim = n_blim;
         c_row0 = n_row0; c_rows = n_rows; c_n0 = n_n0;
+        if (GROUPK) c_kt = n_kt;
         ++ti;
         fetch_next_tile(ti + 1);
 #pragma unroll
@@ -500,6 +522,36 @@ void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int
                        static_cast<bf16_t*>(GU), ntn);
 }
 
+// dw[e] = 0 for every expert without rows (the persistent weight-gradient kernel gives them no tiles)
+__global__ __launch_bounds__(256) void wgrad_zero_empty_kernel(const int32_t* __restrict__ offsets, size_t per_expert,
+                                                               bf16_t* __restrict__ dw) {
+    const int e = blockIdx.y;
+    if (offsets[e + 1] - offsets[e] > 0) return;
+    u32x4* dst = reinterpret_cast<u32x4*>(dw + (size_t)e * per_expert);   // per_expert is a multiple of 8
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < per_expert / 8; i += (size_t)gridDim.x * 256)
+        dst[i] = u32x4{0u, 0u, 0u, 0u};
+}
+
+template <int BM, int BN, int WGM, int WGN>
+void launch_persist_groupk(const void* A, const void* B, const int32_t* offsets, int E, int M, int N, int ld,
+                           void* C, hipStream_t s) {
+    constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
+    auto kern = gemm_bf16_persist_kernel<BM, BN, WGM, WGN, 0, true>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)smem);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(wgrad_zero_empty_kernel, dim3(64, E), dim3(256), 0, s, offsets, (size_t)M * N,
+                       static_cast<bf16_t*>(C));
+    const long long tiles = (long long)E * ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    const int grid = (int)min((long long)persist_grid(), (tiles + 7) / 8 * 8);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A), offsets, E, N,
+                       ld, static_cast<const bf16_t*>(B), static_cast<const bf16_t*>(B), static_cast<bf16_t*>(C),
+                       static_cast<bf16_t*>(nullptr), M);
+}
+
 template <int BM, int BN, int WGM, int WGN>
 void run_persist_pair(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                       const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm, int phase,
@@ -519,6 +571,12 @@ bool launch_grouped_nt(const void* A, const int32_t* offsets, int r_max, int E, 
     if (K < 128 || K % 64 || N % 8) return false;
     launch_persist<256, 256, 2, 4, 0>(A, offsets, r_max, E, N, K, B, nullptr, C, nullptr, s);
     return true;
+}
+
+// dw [E, M, N] = per expert a_t[:, seg_e] . b_t[:, seg_e]^T (see WgradSched); M, N multiples of 8, ld of 64
+void launch_persist_wgrad(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
+                          void* dw, hipStream_t s) {
+    launch_persist_groupk<256, 256, 2, 4>(a_t, b_t, offsets, E, M, N, ld, dw, s);
 }
 
 // dg | du [rows, 2N] from dh = A . B[e]^T (never stored) and the saved pre-activations gu [rows, 2N]

@@ -333,8 +333,8 @@ void run_pipe3_pair(const void* x_perm, const int32_t* offsets, int r_max, int H
 
 }  // namespace
 
-void launch_wgrad_gemm(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
-                       void* dw, hipStream_t s) {
+void launch_pipe3_wgrad(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
+                        void* dw, hipStream_t s) {
     launch_pipe3_groupk<256, 256, 2, 4>(a_t, b_t, offsets, E, M, N, ld, dw, s);
 }
 

@@ -76,7 +76,7 @@ def _ffn_backward_case(H, F, E, counts, seed):
     return inp, offsets, R, x, dy, want
 
 
-def _run_ffn_backward(inp, offsets, R, x, dy, r_pad=0, saved=False):
+def _run_ffn_backward(inp, offsets, R, x, dy, r_pad=0, saved=False, variant=0):
     import torch
     import paper_2504_14960_amd as moe
     E, F, H = inp["w_gate"].shape
@@ -115,7 +115,11 @@ def _run_ffn_backward(inp, offsets, R, x, dy, r_pad=0, saved=False):
     dxp = torch.zeros((r_max, H), **bf)
     dwg, dwu, dwd = torch.full((E, F, H), 7.0, **bf), torch.full((E, F, H), 7.0, **bf), torch.full((E, H, F), 7.0, **bf)
     ws = torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda")
-    moe.grouped_gemm_swiglu_backward(dx_in, h, gu, dy_in, off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
+    moe.set_option("gemm_variant", variant)      # 31: weight gradients by the one-workgroup-per-tile kernel
+    try:
+        moe.grouped_gemm_swiglu_backward(dx_in, h, gu, dy_in, off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
+    finally:
+        moe.set_option("gemm_variant", 0)
     torch.cuda.synchronize()
     # the transposes are plain copies: check them bit for bit against the host
     np.testing.assert_array_equal(to_host(wd_t), np.ascontiguousarray(inp["w_down"].transpose(0, 2, 1)))
@@ -139,13 +143,15 @@ def _assert_grad_close(got, ref, what):
     (256, 384, 6, [700, 0, 1, 300, 513, 86]),      # ragged tiles, an empty expert, a 1-row expert
     (128, 128, 3, [64, 130, 5]),                   # smallest supported sizes
     (384, 256, 64, None),                          # many small experts
+    (640, 384, 2, [1300, 77]),                     # several M- and N-tiles per expert, ragged last tiles
 ])
-@pytest.mark.parametrize("saved", [False, True], ids=["recompute", "saved_gu"])
-def test_expert_ffn_backward_against_oracle(H, F, E, counts, saved):
+@pytest.mark.parametrize("saved,variant", [(False, 0), (True, 0), (True, 31)],
+                         ids=["recompute", "saved_gu", "saved_gu_tile_per_workgroup"])
+def test_expert_ffn_backward_against_oracle(H, F, E, counts, saved, variant):
     if counts is None:
         counts = np.random.default_rng(12).integers(0, 90, size=E).tolist()
     inp, offsets, R, x, dy, want = _ffn_backward_case(H, F, E, counts, 8000 + H + E)
-    dx, dwg, dwu, dwd = _run_ffn_backward(inp, offsets, R, x, dy, r_pad=9, saved=saved)
+    dx, dwg, dwu, dwd = _run_ffn_backward(inp, offsets, R, x, dy, r_pad=9, saved=saved, variant=variant)
     assert (values(dx)[R:] == 0).all()                     # rows past the kept ones untouched
     _assert_grad_close(dx[:R], want[0], "dx_perm")
     _assert_grad_close(dwg, want[1], "dw_gate")
