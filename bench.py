@@ -314,32 +314,44 @@ def main():
         "context": "the paper reports 49.3 % (Mixtral 8x22B) and 39.0 % (Qwen2-57B-A14B) MFU for whole training "
                    "steps on H100 clusters: other hardware, other scope, shown for orientation only",
     }
-    if not args.no_probe and bf16 and not fp8:
+    if not args.no_probe and bf16:
         # the bare inner loop of the grouped GEMM (MFMA + LDS fragment reads, nothing else) on this machine, with
         # all-zero operands and with operands distributed like the workload's: the second is what power
-        # management lets dense bf16 MFMA sustain here, the practical ceiling under roofline.peak
+        # management lets the dense MFMA sustain here, the practical ceiling under roofline.peak
         from moe_inputs import make_tokens
         nwg, iters = 256, 20000
         sink = torch.empty(nwg * 256, dtype=torch.float32, device="cuda")
         ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
-        images = {"zeros": np.zeros((512, 64), dtype=np.uint16),
-                  "workload_like": np.concatenate([make_tokens(4242, 256, 64, True, 1.0),
-                                                   make_tokens(4243, 256, 64, True, 0.02)])}
+        like = dev(np.ascontiguousarray(np.concatenate([make_tokens(4242, 512 if fp8 else 256, 64, True, 1.0),
+                                                         make_tokens(4243, 512 if fp8 else 256, 64, True, 0.02)])))
+        if fp8:
+            # the same values as E4M3 codes under per-tensor scales 448 / amax: [256][128] bytes per operand
+            q = torch.empty((2, 32768), dtype=torch.uint8, device="cuda")
+            halves = like.view(2, -1)
+            for i in range(2):
+                a = torch.zeros(1, dtype=torch.float32, device="cuda")
+                moe.fp8_quantize(halves[i], 1.0, q[i], a)
+                moe.fp8_quantize(halves[i], moe.fp8_delayed_scale([float(a.item())]), q[i])
+            images = {"zeros": torch.zeros(65536, dtype=torch.uint8, device="cuda"), "workload_like": q.view(-1)}
+            run_probe, flop = moe.probe_mfma_fp8, 16777216.0
+        else:
+            images = {"zeros": torch.zeros(32768, dtype=torch.int16, device="cuda"), "workload_like": like}
+            run_probe, flop = moe.probe_mfma_bf16, 8388608.0
         probe = {}
-        for nm, img in images.items():
-            d_img = dev(np.ascontiguousarray(img))
-            moe.probe_mfma_bf16(d_img, iters // 10, nwg, sink, ticks)
+        for nm, d_img in images.items():
+            run_probe(d_img, iters // 10, nwg, sink, ticks)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            moe.probe_mfma_bf16(d_img, iters, nwg, sink, ticks)
+            run_probe(d_img, iters, nwg, sink, ticks)
             e1.record()
             torch.cuda.synchronize()
             tk = ticks.cpu().tolist()
-            probe[nm] = {"tflops": round(nwg * iters * 8388608.0 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1),
+            probe[nm] = {"tflops": round(nwg * iters * flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1),
                          "shader_mhz": round(100.0 * tk[0] / max(tk[1], 1), 0)}
-        probe["note"] = ("bare 32x32x16 bf16 MFMA + LDS fragment loop, 256 workgroups x 4 waves, no global traffic: "
-                         "the rate and clock this box sustains; operands ~N(0,1) x N(0,0.02^2) as in the workload")
+        probe["note"] = ("bare MFMA + LDS fragment loop of the grouped GEMM, 256 workgroups x 4 waves, no global traffic: "
+                         "the rate and clock this box sustains; operands ~N(0,1) x N(0,0.02^2) as in the workload"
+                         + (", as E4M3 codes" if fp8 else ""))
         roofline["mfma_probe"] = probe
         roofline["frac_of_probe"] = round(dom["achieved"] / probe["workload_like"]["tflops"], 4)
     if args.ffn_backward and not fp8 and bf16:

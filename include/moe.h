@@ -406,6 +406,11 @@ moe_status_t moe_expert_down_fp8(const void* h_fp8, const int32_t* expert_offset
  */
 moe_status_t moe_probe_mfma_bf16(const void* image, int iters, int workgroups, float* sink,
                                  uint64_t* ticks, moe_stream_t stream);
+/* The same probe for the FP8 path: image = two blocks of [256 rows][128 E4M3
+ * bytes], 32x32x64 FP8 MFMAs; one launch executes workgroups * iters * 16777216
+ * FLOP. */
+moe_status_t moe_probe_mfma_fp8(const void* image, int iters, int workgroups, float* sink,
+                                uint64_t* ticks, moe_stream_t stream);
 
 /* Tuning knobs for experiments (process-wide, not thread-safe; defaults are
  * the tuned ones).  Unknown names return MOE_ERR_INVALID_ARG.  Names:

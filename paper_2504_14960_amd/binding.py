@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
     L.moe_permute_variant_workspace_bytes.argtypes = [i, i, i]
     L.moe_permute_variant.restype = i
     L.moe_permute_variant.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, i, vp, sz, vp]
+    L.moe_probe_mfma_fp8.restype = i
+    L.moe_probe_mfma_fp8.argtypes = [vp, i, i, vp, vp, vp]
     L.moe_probe_mfma_bf16.restype = i
     L.moe_probe_mfma_bf16.argtypes = [vp, i, i, vp, vp, vp]
     L.moe_expert_gate_up_saving.restype = i
@@ -359,6 +361,12 @@ def probe_mfma_bf16(image: torch.Tensor, iters: int, workgroups: int, sink: torc
                     ticks: Optional[torch.Tensor]) -> None:
     assert image.numel() * image.element_size() == 65536 and sink.numel() >= workgroups * 256
     _check(lib().moe_probe_mfma_bf16(_ptr(image), iters, workgroups, _ptr(sink), _ptr(ticks), _stream()))
+
+
+def probe_mfma_fp8(image: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor,
+                   ticks: Optional[torch.Tensor]) -> None:
+    assert image.numel() * image.element_size() == 65536 and sink.numel() >= workgroups * 256
+    _check(lib().moe_probe_mfma_fp8(_ptr(image), iters, workgroups, _ptr(sink), _ptr(ticks), _stream()))
 
 
 def layer_workspace_bytes(T: int, H: int, E: int, K: int, F: int, Fs: int, capacity: int, dtype: int) -> int:

@@ -692,6 +692,18 @@ moe_status_t moe_probe_mfma_bf16(const void* image, int iters, int workgroups, f
     return check_launch(fn);
 }
 
+moe_status_t moe_probe_mfma_fp8(const void* image, int iters, int workgroups, float* sink,
+                                uint64_t* ticks, moe_stream_t stream) {
+    static const char* fn = "moe_probe_mfma_fp8";
+    if (iters < 1 || workgroups < 1 || workgroups > 65536)
+        return fail(MOE_ERR_INVALID_ARG, "%s: need iters >= 1 and 1 <= workgroups <= 65536", fn);
+    REQUIRE_PTR(fn, image);
+    REQUIRE_PTR(fn, sink);
+    launch_probe_mfma_fp8(image, iters, workgroups, sink, reinterpret_cast<unsigned long long*>(ticks),
+                          static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
 moe_status_t moe_set_option(const char* name, int value) {
     if (name && strcmp(name, "router_tile") == 0) {
         if (value != 0 && value != 1 && value != 2 && value != 4)

@@ -116,6 +116,8 @@ void launch_pipe3_wgrad(const void* a_t, const void* b_t, const int32_t* offsets
 // measurement probe: the bare bf16 MFMA + LDS-fragment loop over a 64 KiB operand image
 void launch_probe_mfma_bf16(const void* image, int iters, int workgroups, float* sink, unsigned long long* ticks,
                             hipStream_t s);
+void launch_probe_mfma_fp8(const void* image, int iters, int workgroups, float* sink, unsigned long long* ticks,
+                           hipStream_t s);
 
 // FP8 (E4M3) path of the expert FFN: per-tensor quantisation with amax, and the
 // two grouped GEMMs on quantised operands (phase bits as above)
