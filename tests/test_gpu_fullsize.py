@@ -227,7 +227,7 @@ def test_full_size_fp8_expert_ffn(name):
     assert_close(to_host(y[dev_tok]), y_ref, True, f"fp8 y rows ({name})")
 
 
-@pytest.mark.parametrize("name", ["mixtral8x22b", "mixtral8x22b_g8t8"])
+@pytest.mark.parametrize("name", ["mixtral8x22b", "mixtral8x22b_g8t8", "llama3_8x70b"])
 def test_full_size_ffn_backward(name):
     """The expert FFN's backward at full size, launched as bench.py --ffn-backward does.  dx_perm on sampled rows
     (a row's input gradient depends on that row only); weight gradients on sampled features of sampled experts: the
