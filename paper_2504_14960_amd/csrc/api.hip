@@ -364,7 +364,7 @@ moe_status_t moe_router_backward(const void* x, const void* w_router, const floa
 }
 
 struct BackwardLayout {
-    size_t g, u, dh, dgdu, dy_t, h_t, dgdu_t, x_t, total;
+    size_t g, u, dh, dgdu, dy_t, h_t, dgdu_t, x_t, poff, total;
     int rp_max;
 };
 
@@ -385,6 +385,7 @@ static BackwardLayout backward_layout(int R_max, int H, int F, int E) {
     L.h_t = take((size_t)F * L.rp_max * 2);
     L.dgdu_t = take((size_t)2 * F * L.rp_max * 2);
     L.x_t = take((size_t)H * L.rp_max * 2);
+    L.poff = take((size_t)(E + 1) * 4);
     L.total = o;
     return L;
 }
@@ -491,10 +492,12 @@ moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h,
         if (!launch_grouped_nt(ws + L.dgdu, expert_offsets, R_max, E, H, 2 * F, wgu_t, dx_perm, s))
             return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
         // operands of the weight gradients, transposed with every expert's rows as a zero-padded column segment
-        launch_ragged_transpose(dy_perm, expert_offsets, E, H, L.rp_max, ws + L.dy_t, s);
-        launch_ragged_transpose(h, expert_offsets, E, F, L.rp_max, ws + L.h_t, s);
-        launch_ragged_transpose(ws + L.dgdu, expert_offsets, E, 2 * F, L.rp_max, ws + L.dgdu_t, s);
-        launch_ragged_transpose(x_perm, expert_offsets, E, H, L.rp_max, ws + L.x_t, s);
+        int32_t* poff = reinterpret_cast<int32_t*>(ws + L.poff);
+        launch_ragged_offsets(expert_offsets, E, poff, s);
+        launch_ragged_transpose(dy_perm, expert_offsets, poff, E, H, L.rp_max, ws + L.dy_t, s);
+        launch_ragged_transpose(h, expert_offsets, poff, E, F, L.rp_max, ws + L.h_t, s);
+        launch_ragged_transpose(ws + L.dgdu, expert_offsets, poff, E, 2 * F, L.rp_max, ws + L.dgdu_t, s);
+        launch_ragged_transpose(x_perm, expert_offsets, poff, E, H, L.rp_max, ws + L.x_t, s);
     }
     // with R_max == 0 every segment is empty and the three launches below write zeros without reading
     const int ld = R_max > 0 ? L.rp_max : 64;

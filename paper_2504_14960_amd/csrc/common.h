@@ -95,8 +95,9 @@ bool launch_grouped_nt(const void* A, const int32_t* offsets, int r_max, int E, 
 // dst[b][c][col0 + r] = src[b][r][c], dst rows ld_out elements long
 void launch_transpose_batched(const void* src, int B, int R, int C, void* dst, size_t ld_out, int col0, hipStream_t s);
 // dst [C, rp_max]: rows of expert e of src [rows, C] become the columns of its zero-padded segment
-void launch_ragged_transpose(const void* src, const int32_t* offsets, int E, int C, int rp_max, void* dst,
-                             hipStream_t s);
+void launch_ragged_offsets(const int32_t* offsets, int E, int32_t* poff, hipStream_t s);   // poff [E + 1]
+void launch_ragged_transpose(const void* src, const int32_t* offsets, const int32_t* poff, int E, int C, int rp_max,
+                             void* dst, hipStream_t s);
 // out [rows, 2F] = dg | du from dh [rows, F] and g, u (rows ld_gu elements apart); rows = *n_rows (device)
 void launch_swiglu_backward(const void* dh, const void* g, const void* u, size_t ld_gu, const int32_t* n_rows,
                             int r_max, int F, void* out, hipStream_t s);

@@ -74,27 +74,45 @@ __global__ __launch_bounds__(256) void transpose_batched_kernel(const uint16_t* 
 // padded length of an expert's column segment in the transposed activations
 __device__ __forceinline__ int padded_rows(int n) { return n <= 0 ? 0 : max(128, (n + 63) & ~63); }
 
+// poff[e] = first column of expert e's zero-padded segment (exclusive prefix of the padded row counts), e = 0..E.
+// One workgroup of 256 threads; E <= 256.
+__global__ __launch_bounds__(256) void ragged_offsets_kernel(const int32_t* __restrict__ offsets, int E,
+                                                             int32_t* __restrict__ poff) {
+    __shared__ int scan[2][256];
+    const int tid = threadIdx.x;
+    const int pn = (tid < E) ? padded_rows(offsets[tid + 1] - offsets[tid]) : 0;
+    scan[0][tid] = pn;
+    __syncthreads();
+    int cur = 0;
+    for (int d = 1; d < 256; d <<= 1) {
+        scan[cur ^ 1][tid] = scan[cur][tid] + ((tid >= d) ? scan[cur][tid - d] : 0);
+        cur ^= 1;
+        __syncthreads();
+    }
+    if (tid < E) poff[tid + 1] = scan[cur][tid];
+    if (tid == 0) poff[0] = 0;
+}
+
 // dst[c][poff_e + (r - lo_e)] = src[r][c] for the rows r of expert e; the pad up to
 // padded_rows(n_e) is zero.  One workgroup per (64-column block, 64-row block of the
-// padded axis); the expert of a padded position is found by a scan of the offsets.
+// padded axis); the expert of a padded position is the one whose segment [poff_e,
+// poff_e+1) holds it (segments are multiples of 64, so a block never straddles two).
 __global__ __launch_bounds__(256) void ragged_transpose_kernel(const uint16_t* __restrict__ src,
-                                                               const int32_t* __restrict__ offsets, int E, int C,
+                                                               const int32_t* __restrict__ offsets,
+                                                               const int32_t* __restrict__ poff, int E, int C,
                                                                uint16_t* __restrict__ dst, size_t ldo) {
     __shared__ uint16_t tile[TT][TT + 2];
     __shared__ int seg[3];   // first source row of this block, valid rows from there on, found flag
     const int p0 = blockIdx.y * TT, c0 = blockIdx.x * TT;
-    if (threadIdx.x == 0) {
-        int poff = 0;
-        seg[2] = 0;
-        for (int e = 0; e < E; ++e) {
-            const int lo = offsets[e], n = offsets[e + 1] - lo, pn = padded_rows(n);
-            if (p0 < poff + pn) {
-                seg[0] = lo + (p0 - poff);
-                seg[1] = n - (p0 - poff);   // may be <= 0: a block of pure padding
-                seg[2] = 1;
-                break;
-            }
-            poff += pn;
+    if (threadIdx.x == 0) seg[2] = 0;
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 256) {
+        const int lo_p = poff[e], hi_p = poff[e + 1];
+        if (lo_p <= p0 && p0 < hi_p) {   // at most one expert
+            const int lo = offsets[e], n = offsets[e + 1] - lo;
+            seg[0] = lo + (p0 - lo_p);
+            seg[1] = n - (p0 - lo_p);   // may be <= 0: a block of pure padding
+            seg[2] = 1;
         }
     }
     __syncthreads();
@@ -153,12 +171,17 @@ void launch_transpose_batched(const void* src, int B, int R, int C, void* dst, s
                        static_cast<const uint16_t*>(src), R, C, static_cast<uint16_t*>(dst), ldo, col0);
 }
 
-// rp_max: the static bound on the padded axis (a multiple of 64); blocks past the real padded length exit
-void launch_ragged_transpose(const void* src, const int32_t* offsets, int E, int C, int rp_max, void* dst,
-                             hipStream_t s) {
+void launch_ragged_offsets(const int32_t* offsets, int E, int32_t* poff, hipStream_t s) {
+    hipLaunchKernelGGL(ragged_offsets_kernel, dim3(1), dim3(256), 0, s, offsets, E, poff);
+}
+
+// rp_max: the static bound on the padded axis (a multiple of 64); blocks past the real padded length exit.
+// poff: the E + 1 segment starts written by launch_ragged_offsets
+void launch_ragged_transpose(const void* src, const int32_t* offsets, const int32_t* poff, int E, int C, int rp_max,
+                             void* dst, hipStream_t s) {
     if (rp_max <= 0 || C <= 0) return;
     hipLaunchKernelGGL(ragged_transpose_kernel, dim3((C + TT - 1) / TT, rp_max / TT), dim3(256), 0, s,
-                       static_cast<const uint16_t*>(src), offsets, E, C, static_cast<uint16_t*>(dst),
+                       static_cast<const uint16_t*>(src), offsets, poff, E, C, static_cast<uint16_t*>(dst),
                        (size_t)rp_max);
 }
 
