@@ -9,6 +9,7 @@ patterns (bf16 configs); the C side widens either exactly to double.
 from __future__ import annotations
 
 import ctypes as C
+import os
 from typing import Optional, Tuple
 
 import numpy as np
@@ -21,7 +22,9 @@ _lib = None
 def lib() -> C.CDLL:
     global _lib
     if _lib is None:
-        L = C.CDLL(_build())
+        # MOE_ORACLE_LIB: another build of the same sources, used only by tests/test_oracle_mutations.py to show
+        # that the pins reject an oracle with a planted mistake
+        L = C.CDLL(os.environ.get("MOE_ORACLE_LIB") or _build())
         L.oracle_num_threads.restype = C.c_int
         L.oracle_capacity.restype = C.c_int
         L.oracle_capacity.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int]
