@@ -148,6 +148,8 @@ def test_experts_fp8_h_equals_the_bf16_oracle_on_dequantised_operands_and_scales
     deq = lambda q, s: f32_to_bf16_bits((oracle.fp8_decode(q) / s).astype(np.float32))
     y_ref, h_ref = oracle.experts(deq(xq, sx), offsets, deq(wq[0], sw), deq(wq[1], sw), deq(wq[2], sw), want_h=True)
     np.testing.assert_allclose(res.h_val, h_ref, rtol=1e-12, atol=1e-300)
+    # the recorded amax is that of h itself, not of h times its scale (the next step's scale is 448 / amax)
+    assert res.amax_h == np.abs(res.h_val).max() and sh != 1.0
     # second GEMM runs on the quantised h
     hq_val = oracle.fp8_decode(res.hq) / sh
     for e in range(E):

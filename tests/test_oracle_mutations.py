@@ -48,6 +48,13 @@ MUTANTS = [
     ("router backward: dW_g and dx swapped operands", "moe_oracle.c",
      "for (int t = 0; t < T; ++t) acc += dlogits[(size_t)t * E + e] * ld(x, (size_t)t * H + n, dt);",
      "for (int t = 0; t < T; ++t) acc += dlogits[(size_t)t * E + e] * ld(x, (size_t)t * H + (n + 1) % H, dt);", ["test_oracle_backward.py"]),
+    ("fp8 experts: up projection dequantised with the gate's factor", "moe_oracle_fp8.c", "u *= dq_up;", "u *= dq_gate;", ["test_oracle_fp8.py"]),
+    ("fp8 experts: SiLU applied after the dequantisation of the wrong operand", "moe_oracle_fp8.c", "double hv = (g / (1.0 + exp(-g))) * u;",
+     "double hv = (u / (1.0 + exp(-u))) * g;", ["test_oracle_fp8.py"]),
+    ("fp8 experts: h quantised without its scale", "moe_oracle_fp8.c", "volatile float p = (float)hv * scale_h;", "volatile float p = (float)hv;",
+     ["test_oracle_fp8.py"]),
+    ("fp8 experts: amax of the quantised instead of the real h", "moe_oracle_fp8.c", "if (fabs(hv) > am) am = fabs(hv);",
+     "if (fabs(hv * scale_h) > am) am = fabs(hv * scale_h);", ["test_oracle_fp8.py"]),
     ("fp8: delayed scale with the margin's sign flipped", "moe_oracle_fp8.c", "ldexp(1.0, margin)", "ldexp(1.0, -margin)", ["test_oracle_fp8.py"]),
     ("fp8: history maximum replaced by the last entry", "moe_oracle_fp8.c", "if (amax_history[i] > m && isfinite(amax_history[i])) m = amax_history[i];",
      "if (isfinite(amax_history[i])) m = amax_history[i];", ["test_oracle_fp8.py"]),
