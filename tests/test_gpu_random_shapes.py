@@ -96,3 +96,58 @@ def test_dispatch_combine_and_their_backward_on_random_shapes(seed):
         torch.cuda.synchronize()
         dx_ref = oracle.permute_backward(values(to_host(dy_perm)), want.row_of_assign, T, K)
         assert_close(to_host(dx), dx_ref, bf16, f"dx {tag}")
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_expert_ffn_forward_and_backward_on_random_shapes(seed):
+    """Odd layer sizes and ragged counts through the default kernels: sizes that are multiples of 128 take the
+    persistent MFMA kernels (forward, forward keeping g | u, backward), the others the guarded fallback (forward)."""
+    import torch
+    import paper_2504_14960_amd as moe
+    from moe_inputs import get_config, make_layer_inputs
+    rng = np.random.default_rng(seed)
+    for case in range(6):
+        H = int(rng.choice([64, 72, 128, 256, 320, 384]))
+        F = int(rng.choice([64, 136, 128, 256, 384, 448]))
+        E = int(rng.choice([1, 3, 8, 40]))
+        counts = [int(c) for c in rng.choice([0, 1, 31, 64, 130, 257, 300], size=E)]
+        tag = f"case {case}: H={H} F={F} E={E} counts={counts}"
+        cfg = get_config("mixtral8x7b").scaled(T=8, H=H, E=E, K=1, F=F, seed=7000 + 10 * seed + case)
+        inp = make_layer_inputs(cfg, ["w_gate", "w_up", "w_down"])
+        offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+        R = int(offsets[-1])
+        if R == 0:
+            continue
+        x = make_tokens(seed * 100 + case, R, H, bf16=True)
+        y_ref, h_ref = oracle.experts(x, offsets, inp["w_gate"], inp["w_up"], inp["w_down"], want_h=True)
+        bf = dict(dtype=torch.bfloat16, device="cuda")
+        d_x, off = to_dev(x), to_dev(offsets)
+        wg, wu, wd = to_dev(inp["w_gate"]), to_dev(inp["w_up"]), to_dev(inp["w_down"])
+        h, y = torch.zeros((R, F), **bf), torch.zeros((R, H), **bf)
+        moe.grouped_gemm_swiglu(d_x, off, wg, wu, wd, h, y)
+        torch.cuda.synchronize()
+        assert_close(to_host(h), h_ref, True, f"h {tag}")
+        assert_close(to_host(y), y_ref, True, f"y_perm {tag}")
+        if H % 128 or F % 128:
+            continue
+        # training forward + backward at the supported sizes
+        gu, h2 = torch.zeros((R, 2 * F), **bf), torch.zeros((R, F), **bf)
+        moe.expert_gate_up_saving(d_x, off, wg, wu, h2, gu)
+        torch.cuda.synchronize()
+        assert torch.equal(h2, h), tag
+        dy = make_tokens(seed * 100 + 50 + case, R, H, bf16=True)
+        want = oracle.experts_backward(x, offsets, inp["w_gate"], inp["w_up"], inp["w_down"], values(dy))
+        wgu_t, wd_t = torch.empty((E, H, 2 * F), **bf), torch.empty((E, F, H), **bf)
+        moe.expert_weights_transpose(wg, wu, wd, wgu_t, wd_t)
+        dxp = torch.zeros((R, H), **bf)
+        dwg, dwu, dwd = torch.empty((E, F, H), **bf), torch.empty((E, F, H), **bf), torch.empty((E, H, F), **bf)
+        ws = torch.empty(moe.expert_backward_workspace_bytes(R, H, F, E) + 256, dtype=torch.uint8, device="cuda")
+        ws.random_(0, 255)
+        moe.grouped_gemm_swiglu_backward(d_x, h, gu, to_dev(dy), off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
+        torch.cuda.synchronize()
+        for got, ref, what in ((dxp, want[0], "dx_perm"), (dwg, want[1], "dw_gate"), (dwu, want[2], "dw_up"), (dwd, want[3], "dw_down")):
+            g, r = values(to_host(got)), np.asarray(ref, dtype=np.float64)
+            d = g - r
+            assert np.isfinite(g).all(), f"{what} {tag}"
+            assert np.abs(d).max() <= 3e-2 * np.abs(r).max() + 1e-30, f"{what} {tag}: max|d| {np.abs(d).max():.3e}"
+            assert np.linalg.norm(d) <= 1e-2 * np.linalg.norm(r) + 1e-30, f"{what} {tag}"
