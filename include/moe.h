@@ -417,7 +417,10 @@ moe_status_t moe_probe_mfma_fp8(const void* image, int iters, int workgroups, fl
  * "gemm_variant" (0 = auto); "gemm_workgroups" (workgroups launched by the
  * persistent grouped-GEMM kernels; 0 = one per compute unit, values below 8
  * are raised to 8); "router_tile" (16-token blocks per router workgroup: 1, 2
- * or 4; 0 = chosen from T and E). */
+ * or 4; 0 = chosen from T and E); "wgrad_rowmajor" (1 = the expert FFN's backward
+ * forms the weight gradients straight from the row-major activations with
+ * transposing LDS loads instead of from transposed copies: about 1.8x slower
+ * weight-gradient GEMMs, no ragged transposes; default 0). */
 moe_status_t moe_set_option(const char* name, int value);
 
 #ifdef __cplusplus

@@ -12,6 +12,7 @@ namespace moe {
 
 static thread_local char g_err[512] = "";
 static int g_gemm_variant = 0;
+static int g_wgrad_rowmajor = 0;   // 1: weight gradients straight from the row-major activations (slower, no transposed copies)
 
 moe_status_t fail(moe_status_t st, const char* fmt, ...) {
     va_list ap;
@@ -364,7 +365,7 @@ moe_status_t moe_router_backward(const void* x, const void* w_router, const floa
 }
 
 struct BackwardLayout {
-    size_t g, u, dh, dgdu, dy_t, h_t, dgdu_t, x_t, poff, total;
+    size_t g, u, dh, dgdu, dy_t, h_t, dgdu_t, x_t, poff, zero, total;
     int rp_max;
 };
 
@@ -386,6 +387,7 @@ static BackwardLayout backward_layout(int R_max, int H, int F, int E) {
     L.dgdu_t = take((size_t)2 * F * L.rp_max * 2);
     L.x_t = take((size_t)H * L.rp_max * 2);
     L.poff = take((size_t)(E + 1) * 4);
+    L.zero = take(1024);
     L.total = o;
     return L;
 }
@@ -491,6 +493,19 @@ moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h,
         if (!ok) return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
         if (!launch_grouped_nt(ws + L.dgdu, expert_offsets, R_max, E, H, 2 * F, wgu_t, dx_perm, s))
             return fail(MOE_ERR_UNSUPPORTED, "%s: no kernel for H=%d F=%d", fn, H, F);
+    }
+    const bool pipe3 = g_gemm_variant == 30 || g_gemm_variant == 31;
+    if (g_wgrad_rowmajor && !pipe3) {
+        // weight gradients straight from the row-major activations; rows past an expert's end read a zero row
+        if (R_max > 0) {
+            launch_fill_i32(reinterpret_cast<int32_t*>(ws + L.zero), 256, 0, 0, s);
+            launch_persist_wgrad_rowmajor(dy_perm, H, h, F, expert_offsets, E, H, F, ws + L.zero, dw_down, s);
+            launch_persist_wgrad_rowmajor(ws + L.dgdu, 2 * F, x_perm, H, expert_offsets, E, F, H, ws + L.zero, dw_gate, s);
+            launch_persist_wgrad_rowmajor(ws + L.dgdu + (size_t)F * 2, 2 * F, x_perm, H, expert_offsets, E, F, H,
+                                          ws + L.zero, dw_up, s);
+            return check_launch(fn);
+        }
+    } else if (R_max > 0) {
         // operands of the weight gradients, transposed with every expert's rows as a zero-padded column segment
         int32_t* poff = reinterpret_cast<int32_t*>(ws + L.poff);
         launch_ragged_offsets(expert_offsets, E, poff, s);
@@ -502,7 +517,7 @@ moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h,
     // with R_max == 0 every segment is empty and the three launches below write zeros without reading
     const int ld = R_max > 0 ? L.rp_max : 64;
     // "gemm_variant" 30 / 31 select the one-workgroup-per-tile kernel, anything else the persistent one
-    auto wgrad = (g_gemm_variant == 30 || g_gemm_variant == 31) ? launch_pipe3_wgrad : launch_persist_wgrad;
+    auto wgrad = pipe3 ? launch_pipe3_wgrad : launch_persist_wgrad;
     wgrad(ws + L.dy_t, ws + L.h_t, expert_offsets, E, H, F, ld, dw_down, s);
     wgrad(ws + L.dgdu_t, ws + L.x_t, expert_offsets, E, F, H, ld, dw_gate, s);
     wgrad(ws + L.dgdu_t + (size_t)F * ld * 2, ws + L.x_t, expert_offsets, E, F, H, ld, dw_up, s);
@@ -708,6 +723,10 @@ moe_status_t moe_probe_mfma_fp8(const void* image, int iters, int workgroups, fl
 }
 
 moe_status_t moe_set_option(const char* name, int value) {
+    if (name && strcmp(name, "wgrad_rowmajor") == 0) {
+        g_wgrad_rowmajor = value != 0;
+        return MOE_OK;
+    }
     if (name && strcmp(name, "router_tile") == 0) {
         if (value != 0 && value != 1 && value != 2 && value != 4)
             return fail(MOE_ERR_INVALID_ARG, "moe_set_option: router_tile must be 0, 1, 2 or 4");

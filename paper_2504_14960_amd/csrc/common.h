@@ -111,6 +111,9 @@ bool launch_gate_up_saving(const void* x_perm, const int32_t* offsets, int r_max
 // persistent: one workgroup per compute unit; pipe3: one workgroup per output tile
 void launch_persist_wgrad(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
                           void* dw, hipStream_t s);
+// the same product straight from the row-major activations a [rows, lda], b [rows, ldb] (no transposed copies)
+void launch_persist_wgrad_rowmajor(const void* a, int lda, const void* b, int ldb, const int32_t* offsets, int E,
+                                   int M, int N, const void* zero_row, void* dw, hipStream_t s);
 void launch_pipe3_wgrad(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
                         void* dw, hipStream_t s);
 

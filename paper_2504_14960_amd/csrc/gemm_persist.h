@@ -30,6 +30,7 @@ struct PTile {
     uint32_t b_lim;     // byte offset (from b0 / b1) of the last valid weight row
     int row0, rows, n0;
     int kt;             // k-tiles of this output tile (weight-gradient form; 0 = the launch's common count)
+    int krows;          // row-major weight-gradient form: rows of the expert, i.e. valid length of the contraction
     bool valid;
 };
 
@@ -79,7 +80,7 @@ struct TileSched {
                                          size_t row_bytes, int outn) const {
         constexpr int MG = 8;
         PTile t;
-        t.a = A; t.b0 = B0; t.b1 = B1; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0; t.kt = 0;
+        t.a = A; t.b0 = B0; t.b1 = B1; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0; t.kt = 0; t.krows = 0;
         const int j = wgx + i * nwx;
         const int L = xcd * per + j;
         t.valid = (j < per) && (L < total);
@@ -191,7 +192,7 @@ struct WgradSched {
     __device__ __forceinline__ PTile get(int i, const uint8_t* A, const uint8_t* B, int M, int N, int ld) const {
         constexpr int MG = 8;
         PTile t;
-        t.a = A; t.b0 = B; t.b1 = B; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0; t.kt = 0;
+        t.a = A; t.b0 = B; t.b1 = B; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0; t.kt = 0; t.krows = 0;
         const int j = wgx + i * nwx;
         t.valid = j < total;
         if (!t.valid) return t;
@@ -230,6 +231,98 @@ struct WgradSched {
         t.b1 = t.b0;
         t.a_lim = uni((uint32_t)(t.rows - 1) * (uint32_t)k2);
         t.b_lim = uni((uint32_t)(min(BN, N - t.n0) - 1) * (uint32_t)k2);
+        return t;
+    }
+};
+
+// Schedule of the weight-gradient form on ROW-MAJOR activations: C [E, M, N], for expert e the product
+// A[rows_e, :]^T B[rows_e, :] with A [rows, lda] and B [rows, ldb] as the layer holds them (rows grouped by expert).
+// The contraction runs over the expert's rows in k-tiles of 64 rows; rows past the expert's last one are read from a
+// zero row by the kernel.  Tile order and XCD shares as in WgradSched.  Every tile gets at least two k-tiles (the
+// k stream needs them; the second of a short expert is all zero rows).  Lane l describes experts 4l .. 4l+3.
+template <int BM, int BN>
+struct WgradSchedKM {
+    int lo[4], n[4], pex[4], pend;
+    int mt, nt, tpe, nwx, wgx, part0, part_n, total;
+
+    __device__ __forceinline__ void init(const int32_t* __restrict__ offsets, int E, int M, int N, int lane) {
+        int s_cnt = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = lane * 4 + j;
+            lo[j] = 0;
+            n[j] = 0;
+            if (e < E) {
+                lo[j] = offsets[e];
+                n[j] = max(0, offsets[e + 1] - lo[j]);
+            }
+            s_cnt += n[j] > 0;
+        }
+        int incl_cnt = s_cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int oc = __shfl_up(incl_cnt, d, 64);
+            if (lane >= d) incl_cnt += oc;
+        }
+        pex[0] = incl_cnt - s_cnt;
+#pragma unroll
+        for (int j = 1; j < 4; ++j) pex[j] = pex[j - 1] + (n[j - 1] > 0);
+        pend = incl_cnt;
+        mt = (M + BM - 1) / BM;
+        nt = (N + BN - 1) / BN;
+        tpe = mt * nt;
+        const int xcd = blockIdx.x & 7;
+        part0 = (int)((long long)xcd * tpe / 8);
+        part_n = (int)((long long)(xcd + 1) * tpe / 8) - part0;
+        total = __builtin_amdgcn_readlane(incl_cnt, 63) * part_n;
+        wgx = blockIdx.x >> 3;
+        nwx = (gridDim.x + 7 - xcd) >> 3;
+    }
+
+    // lda, ldb: elements per row of A and B
+    __device__ __forceinline__ PTile get(int i, const uint8_t* A, const uint8_t* B, int M, int N, int lda,
+                                         int ldb) const {
+        constexpr int MG = 8;
+        PTile t;
+        t.a = A; t.b0 = B; t.b1 = B; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0; t.kt = 0; t.krows = 0;
+        const int j = wgx + i * nwx;
+        t.valid = j < total;
+        if (!t.valid) return t;
+        const int qe = j / part_n;
+        int hit = -1, my_lo = 0, my_n = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (n[q] > 0 && pex[q] == qe) {
+                hit = q; my_lo = lo[q]; my_n = n[q];
+            }
+        const uint64_t bal = __ballot(hit >= 0);
+        const int src = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)bal) - 1);
+        const int e = 4 * src + __builtin_amdgcn_readlane(hit, src);
+        const int lo_e = __builtin_amdgcn_readlane(my_lo, src);
+        const int n_e = __builtin_amdgcn_readlane(my_n, src);
+        const int Le = part0 + j - qe * part_n;
+        const int full = (mt / MG) * MG * nt;
+        int m, nn;
+        if (Le < full) {
+            const int g = Le / (MG * nt), rem = Le - g * MG * nt;
+            nn = rem / MG;
+            m = g * MG + rem - nn * MG;
+        } else {
+            const int tail = mt % MG, rem = Le - full;
+            nn = rem / tail;
+            m = (mt / MG) * MG + rem - nn * tail;
+        }
+        t.rows = uni(min(BM, M - m * BM));
+        t.row0 = uni(e * M + m * BM);
+        t.n0 = uni(nn * BN);
+        t.krows = uni(n_e);
+        t.kt = uni(max(2, (n_e + 63) / 64));
+        t.a = uni(A + ((size_t)lo_e * lda + (size_t)m * BM) * 2);
+        t.b0 = uni(B + ((size_t)lo_e * ldb + (size_t)t.n0) * 2);
+        t.b1 = t.b0;
+        // last 16-byte piece of a tile row that still lies inside the matrix row
+        t.a_lim = uni((uint32_t)(t.rows * 2 - 16));
+        t.b_lim = uni((uint32_t)(min(BN, N - t.n0) * 2 - 16));
         return t;
     }
 };

@@ -200,12 +200,21 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_r
 // contracting over its own zero-padded column segment (see WgradSched); `ntn`
 // carries M.  Experts without rows get no tiles here (their gradient is zeroed
 // by wgrad_zero_empty_kernel).
-template <int BM, int BN, int WGM, int WGN, int MODE, bool GROUPK = false>
+//
+// KMAJ (with GROUPK): the same product on the activations AS THE LAYER HOLDS THEM, A [rows, lda] and B0 [rows,
+// ldb] row-major (K carries lda), no transposed copies.  A k-tile is then 64 rows x 256 features (512-byte LDS
+// rows, 16-byte pieces XOR-swizzled by the row), and a fragment's eight contraction values per lane come from two
+// transposing LDS loads (ds_read_b64_tr_b16: the 16 lanes of a group address a 4 x 16 block, four consecutive
+// features each, and lane i receives feature i of the four rows).  Both operands are read the same way, so they
+// agree on the order of the contraction values.  Rows past the expert's last one are fetched from the zero row
+// that GU points at (512 bytes of zeros).
+template <int BM, int BN, int WGM, int WGN, int MODE, bool GROUPK = false, bool KMAJ = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, bf16_t* __restrict__ GU,
-    int ntn) {
+    int ntn, int ldb) {
     static_assert(!GROUPK || MODE == 0, "the weight-gradient form has a plain epilogue");
+    static_assert(!KMAJ || (GROUPK && BM == 256 && BN == 256 && WGM * WGN == 8), "row-major form: 256 x 256 tiles, 8 waves");
     constexpr bool SWIGLU = MODE == 1 || MODE == 2;
     constexpr int BK = 64;
     constexpr int NW = WGM * WGN;
@@ -252,13 +261,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const uint8_t* const B0b = reinterpret_cast<const uint8_t*>(B0);
     const uint8_t* const B1b = SWIGLU ? reinterpret_cast<const uint8_t*>(B1) : B0b;
 
-    typename std::conditional<GROUPK, WgradSched<BM, BN>, TileSched<BM>>::type sched;
+    typename std::conditional<KMAJ, WgradSchedKM<BM, BN>,
+                              typename std::conditional<GROUPK, WgradSched<BM, BN>, TileSched<BM>>::type>::type sched;
     if constexpr (GROUPK)
         sched.init(offsets, E, ntn, N, lane);
     else
         sched.init(offsets, E, ntn, lane);
     auto get_tile = [&](int i) -> PTile {
-        if constexpr (GROUPK)
+        if constexpr (KMAJ)
+            return sched.get(i, Ab, B0b, ntn, N, K, ldb);
+        else if constexpr (GROUPK)
             return sched.get(i, Ab, B0b, ntn, N, K);
         else
             return sched.get(i, Ab, B0b, B1b, N, (size_t)K * 2, OUTN);
@@ -269,6 +281,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     uint32_t c_alim, c_blim, n_alim, n_blim;
     int c_row0, c_rows, c_n0, n_row0, n_rows, n_n0;
     int c_kt = K / BK, n_kt = K / BK;   // k-tiles per output tile: per tile in the weight-gradient form
+    int c_krows = 0, n_krows = 0;       // row-major form: rows of the tile's expert
     bool n_valid;
     {
         const PTile t = get_tile(0);
@@ -276,12 +289,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         c_a = t.a; c_b0 = t.b0; c_b1 = t.b1; c_alim = t.a_lim; c_blim = t.b_lim;
         c_row0 = t.row0; c_rows = t.rows; c_n0 = t.n0;
         if (GROUPK) c_kt = t.kt;
+        if (KMAJ) c_krows = t.krows;
     }
     auto fetch_next_tile = [&](int i) {
         const PTile t = get_tile(i);
         n_a = t.a; n_b0 = t.b0; n_b1 = t.b1; n_alim = t.a_lim; n_blim = t.b_lim;
         n_row0 = t.row0; n_rows = t.rows; n_n0 = t.n0; n_valid = t.valid;
         if (GROUPK) n_kt = t.kt;
+        if (KMAJ) n_krows = t.krows;
     };
     fetch_next_tile(1);
 
@@ -295,6 +310,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const uint32_t step = (uint32_t)RPP * k2;
     const int wbase = (wave * 64 / CPR) * ROWB;
 
+    // row-major form: a pass covers 16 rows of 512 bytes; thread = (row tid / 32, piece tid % 32); the piece it asks
+    // for is XOR-swizzled by the row in units of 32 bytes: a 16-lane group of a transposing read touches 32 bytes
+    // of four consecutive rows, which then lie in the four different quarters of the 128-byte bank window
+    const int km_row = tid >> 5;
+    const uint32_t km_piece = (uint32_t)(((tid & 31) ^ (2 * (km_row & 3))) * 16);
+    const uint8_t* const zero_row = reinterpret_cast<const uint8_t*>(GU) + (tid & 31) * 16;
+    auto fetch_km = [&](int p, const uint8_t* base, uint32_t ld2, uint32_t lim, int rows_left, uint8_t* st) {
+        const int krow = 16 * p + km_row;
+        const uint8_t* src = base + (uint32_t)krow * ld2 + min(km_piece, lim);
+        if (krow >= rows_left) src = zero_row;   // past the expert's last row: contributes nothing
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(st + p * RPP * ROWB + wbase), 16,
+                                         0, 0);
+    };
     auto fetch_a = [&](int p, const uint8_t* base, uint32_t lim, uint8_t* st) {
         const uint32_t off = min(vrow + (uint32_t)p * step, lim) + vswz;  // ragged tail: a valid row again
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + off),
@@ -315,6 +344,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         const uint8_t* b0;
         const uint8_t* b1;
         uint32_t a_lim, b_lim;
+        int rows_left;   // row-major form: valid rows from this k-tile's first row on
     };
     // every tile has at least two k-tiles, so k-tile KT + 1 of the stream is the next tile's second
     auto src = [&](int kk) -> Src {
@@ -322,27 +352,51 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         const bool in_cur = kk < KT;
         const bool use_cur = in_cur || !n_valid;  // past the last tile: its last k-tile again, never used
         const int k = in_cur ? kk : (n_valid ? kk - KT : KT - 1);
-        const size_t kbyte = (size_t)k * (BK * 2);
+        // a k-tile is 64 elements along the rows, or (row-major form) 64 rows
+        const size_t kbyte_a = KMAJ ? (size_t)k * 64 * ((size_t)K * 2) : (size_t)k * (BK * 2);
+        const size_t kbyte_b = KMAJ ? (size_t)k * 64 * ((size_t)ldb * 2) : (size_t)k * (BK * 2);
         Src s;
-        s.a = (use_cur ? c_a : n_a) + kbyte;
-        s.b0 = (use_cur ? c_b0 : n_b0) + kbyte;
-        s.b1 = (use_cur ? c_b1 : n_b1) + kbyte;
+        s.a = (use_cur ? c_a : n_a) + kbyte_a;
+        s.b0 = (use_cur ? c_b0 : n_b0) + kbyte_b;
+        s.b1 = (use_cur ? c_b1 : n_b1) + kbyte_b;
         s.a_lim = use_cur ? c_alim : n_alim;
         s.b_lim = use_cur ? c_blim : n_blim;
+        s.rows_left = KMAJ ? (use_cur ? c_krows : n_krows) - k * 64 : 0;
         return s;
     };
     // load i of a period: i < PB -> pass i of the weight tile (source se, slot
     // ld_b), else pass i - PB of the activation tile (source sl, slot ld_a)
     auto fetch_one = [&](int i, const Src& se, const Src& sl, uint8_t* ld_b, uint8_t* ld_a) {
-        if (i < PB)
-            fetch_b(i, se.b0, se.b1, se.b_lim, ld_b);
-        else
-            fetch_a(i - PB, sl.a, sl.a_lim, ld_a);
+        if constexpr (KMAJ) {
+            if (i < PB)
+                fetch_km(i, se.b0, (uint32_t)ldb * 2u, se.b_lim, se.rows_left, ld_b);
+            else
+                fetch_km(i - PB, sl.a, k2, sl.a_lim, sl.rows_left, ld_a);
+        } else {
+            if (i < PB)
+                fetch_b(i, se.b0, se.b1, se.b_lim, ld_b);
+            else
+                fetch_a(i - PB, sl.a, sl.a_lim, ld_a);
+        }
     };
 
     const int fr = lane & 31, fk = lane >> 5;
     int a_off[FM], b_off[FN];
     const int f_sw = fr & 7;  // every fragment row is fr mod 8 (fragments start at multiples of 32)
+    if constexpr (KMAJ) {
+        // lane (group g = lane / 16, s = lane % 16) addresses row 4 (g / 2) + s / 4 of an 8-row block, features
+        // 16 (g % 2) + 4 (s % 4) .. + 3 of the fragment's 32; its row decides the swizzle of the 64-byte unit
+        const int g = lane >> 4, sl = lane & 15;
+        const int r8 = 4 * (g >> 1) + (sl >> 2);
+        const int piece_in = 2 * (g & 1) + ((sl & 3) >> 1);   // 16-byte piece inside the fragment's 64 bytes
+        const int byte_in = 8 * (sl & 1);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+            a_off[i] = r8 * 512 + ((((wm * WM + i * 32) >> 3) + piece_in) ^ (2 * (r8 & 3))) * 16 + byte_in;
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            b_off[j] = r8 * 512 + ((((wn * WN + j * 32) >> 3) + piece_in) ^ (2 * (r8 & 3))) * 16 + byte_in;
+    } else {
 #pragma unroll
     for (int i = 0; i < FM; ++i) a_off[i] = (wm * WM + i * 32 + fr) * ROWB;
 #pragma unroll
@@ -356,6 +410,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         }
         b_off[j] = r * ROWB;
     }
+    }
 
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -367,6 +422,21 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
 
     bf16x8 af[2][FM], bfg[2][FN];
     auto read_one = [&](const uint8_t* sa, const uint8_t* sb, int s, int buf, int q) {
+        if constexpr (KMAJ) {
+            // k-step s = rows 16 s .. 16 s + 15: one transposing load for its first 8 rows, one for the last 8
+            typedef __attribute__((ext_vector_type(4))) short s16x4;
+            typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+            const uint8_t* p = (q < FM ? sa + a_off[q] : sb + b_off[q - FM]) + s * (16 * 512);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * 512));
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            if (q < FM)
+                af[buf][q] = __builtin_bit_cast(bf16x8, v);
+            else
+                bfg[buf][q - FM] = __builtin_bit_cast(bf16x8, v);
+            return;
+        }
         const int c = ((2 * s + fk) ^ f_sw) << 4;
         if (q < FM)
             af[buf][q] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sa + a_off[q] + c));
@@ -473,6 +543,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         c_a = n_a; c_b0 = n_b0; c_b1 = n_b1; c_alim = n_alim; c_blim = n_blim;
         c_row0 = n_row0; c_rows = n_rows; c_n0 = n_n0;
         if (GROUPK) c_kt = n_kt;
+        if (KMAJ) c_krows = n_krows;
         ++ti;
         fetch_next_tile(ti + 1);
 #pragma unroll
@@ -519,7 +590,7 @@ void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int
     const int grid = min(persist_grid(), grid_for(r_max, E, BM, ntn));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A), offsets, E, N,
                        K, static_cast<const bf16_t*>(B0), static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C),
-                       static_cast<bf16_t*>(GU), ntn);
+                       static_cast<bf16_t*>(GU), ntn, 0);
 }
 
 // dw[e] = 0 for every expert without rows (the persistent weight-gradient kernel gives them no tiles)
@@ -549,7 +620,28 @@ void launch_persist_groupk(const void* A, const void* B, const int32_t* offsets,
     const int grid = (int)min((long long)persist_grid(), (tiles + 7) / 8 * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A), offsets, E, N,
                        ld, static_cast<const bf16_t*>(B), static_cast<const bf16_t*>(B), static_cast<bf16_t*>(C),
-                       static_cast<bf16_t*>(nullptr), M);
+                       static_cast<bf16_t*>(nullptr), M, 0);
+}
+
+// weight gradients straight from the row-major activations (no transposed copies): see the kernel's KMAJ form
+template <int BM, int BN, int WGM, int WGN>
+void launch_persist_groupk_rowmajor(const void* A, int lda, const void* B, int ldb, const int32_t* offsets, int E,
+                                    int M, int N, const void* zero_row, void* C, hipStream_t s) {
+    constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
+    auto kern = gemm_bf16_persist_kernel<BM, BN, WGM, WGN, 0, true, true>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)smem);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(wgrad_zero_empty_kernel, dim3(64, E), dim3(256), 0, s, offsets, (size_t)M * N,
+                       static_cast<bf16_t*>(C));
+    const long long tiles = (long long)E * ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    const int grid = (int)min((long long)persist_grid(), (tiles + 7) / 8 * 8);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A), offsets, E, N,
+                       lda, static_cast<const bf16_t*>(B), static_cast<const bf16_t*>(B), static_cast<bf16_t*>(C),
+                       static_cast<bf16_t*>(const_cast<void*>(zero_row)), M, ldb);
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -577,6 +669,13 @@ bool launch_grouped_nt(const void* A, const int32_t* offsets, int r_max, int E, 
 void launch_persist_wgrad(const void* a_t, const void* b_t, const int32_t* offsets, int E, int M, int N, int ld,
                           void* dw, hipStream_t s) {
     launch_persist_groupk<256, 256, 2, 4>(a_t, b_t, offsets, E, M, N, ld, dw, s);
+}
+
+// dw [E, M, N] = per expert A[rows_e, 0:M]^T . B[rows_e, 0:N], A [rows, lda] and B [rows, ldb] row-major; M, N
+// multiples of 8 and lda, ldb multiples of 8; zero_row: 512 bytes of zeros
+void launch_persist_wgrad_rowmajor(const void* a, int lda, const void* b, int ldb, const int32_t* offsets, int E,
+                                   int M, int N, const void* zero_row, void* dw, hipStream_t s) {
+    launch_persist_groupk_rowmajor<256, 256, 2, 4>(a, lda, b, ldb, offsets, E, M, N, zero_row, dw, s);
 }
 
 // dg | du [rows, 2N] from dh = A . B[e]^T (never stored) and the saved pre-activations gu [rows, 2N]

@@ -115,11 +115,14 @@ def _run_ffn_backward(inp, offsets, R, x, dy, r_pad=0, saved=False, variant=0):
     dxp = torch.zeros((r_max, H), **bf)
     dwg, dwu, dwd = torch.full((E, F, H), 7.0, **bf), torch.full((E, F, H), 7.0, **bf), torch.full((E, H, F), 7.0, **bf)
     ws = torch.empty(moe.expert_backward_workspace_bytes(r_max, H, F, E) + 256, dtype=torch.uint8, device="cuda")
-    moe.set_option("gemm_variant", variant)      # 31: weight gradients by the one-workgroup-per-tile kernel
+    # 31: weight gradients by the one-workgroup-per-tile kernel; -1: straight from the row-major activations
+    moe.set_option("gemm_variant", max(variant, 0))
+    moe.set_option("wgrad_rowmajor", int(variant == -1))
     try:
         moe.grouped_gemm_swiglu_backward(dx_in, h, gu, dy_in, off, wg, wu, wgu_t, wd_t, dxp, dwg, dwu, dwd, ws)
     finally:
         moe.set_option("gemm_variant", 0)
+        moe.set_option("wgrad_rowmajor", 0)
     torch.cuda.synchronize()
     # the transposes are plain copies: check them bit for bit against the host
     np.testing.assert_array_equal(to_host(wd_t), np.ascontiguousarray(inp["w_down"].transpose(0, 2, 1)))
@@ -145,8 +148,8 @@ def _assert_grad_close(got, ref, what):
     (384, 256, 64, None),                          # many small experts
     (640, 384, 2, [1300, 77]),                     # several M- and N-tiles per expert, ragged last tiles
 ])
-@pytest.mark.parametrize("saved,variant", [(False, 0), (True, 0), (True, 31)],
-                         ids=["recompute", "saved_gu", "saved_gu_tile_per_workgroup"])
+@pytest.mark.parametrize("saved,variant", [(False, 0), (True, 0), (True, 31), (True, -1)],
+                         ids=["recompute", "saved_gu", "saved_gu_tile_per_workgroup", "saved_gu_rowmajor_wgrad"])
 def test_expert_ffn_backward_against_oracle(H, F, E, counts, saved, variant):
     if counts is None:
         counts = np.random.default_rng(12).integers(0, 90, size=E).tolist()
