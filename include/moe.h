@@ -299,6 +299,39 @@ moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h,
 size_t moe_layer_workspace_bytes(int T, int H, int E, int K, int F, int Fs, int capacity,
                                  moe_dtype_t dt);
 
+/*
+ * The training step of the layer in two calls (bf16, no shared expert; Section
+ * 3.3: the backward workflow mirrors the forward one).
+ *
+ * moe_layer_forward_train is moe_layer_forward with the first expert GEMM
+ * keeping its pre-activations: gu [R_max, 2F] = (g | u) (caller-owned, R_max =
+ * moe_max_rows(T, K, E, capacity)).  Same workspace size and layout as
+ * moe_layer_forward with Fs = 0; the workspace must stay untouched until the
+ * backward has run.
+ *
+ * moe_layer_backward takes dy [T,H] and that forward workspace and chains
+ * moe_unpermute_combine_backward, moe_grouped_gemm_swiglu_backward,
+ * moe_router_backward and moe_permute_backward (the router's input gradient
+ * joins the experts' at the last step).  Outputs: dx [T,H] bf16; dw_router
+ * [E,H] and dbias [E] fp32 (either may be NULL); dw_gate, dw_up [E,F,H],
+ * dw_down [E,H,F] bf16.  wgu_t, wd_t: from moe_expert_weights_transpose.  gu
+ * may be NULL (g and u are then recomputed).  H and F multiples of 128.
+ * workspace: moe_layer_backward_workspace_bytes, separate from the forward's.
+ */
+moe_status_t moe_layer_forward_train(const void* x, const void* w_router, const float* logit_bias,
+                                     const void* w_gate, const void* w_up, const void* w_down, int T,
+                                     int H, int E, int K, int F, int renormalize, int capacity, void* y,
+                                     void* gu, void* workspace, size_t workspace_bytes,
+                                     moe_stream_t stream);
+size_t moe_layer_backward_workspace_bytes(int T, int H, int E, int K, int F, int capacity);
+moe_status_t moe_layer_backward(const void* x, const void* w_router, const void* w_gate,
+                                const void* w_up, const void* wgu_t, const void* wd_t, const void* dy,
+                                int T, int H, int E, int K, int F, int renormalize, int capacity,
+                                const void* forward_workspace, const void* gu, void* dx,
+                                float* dw_router, float* dbias, void* dw_gate, void* dw_up,
+                                void* dw_down, void* workspace, size_t workspace_bytes,
+                                moe_stream_t stream);
+
 /* Where moe_layer_forward keeps its intermediates inside `workspace`, for
  * tests and profiling.  Writes 11 byte offsets into byte_offsets[0..10], in
  * this order: logits [T,E] f32, topk_idx [T,K] i32, topk_gate [T,K] f32,

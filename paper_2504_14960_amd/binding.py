@@ -82,6 +82,12 @@ def lib() -> C.CDLL:
     L.moe_permute_variant_workspace_bytes.argtypes = [i, i, i]
     L.moe_permute_variant.restype = i
     L.moe_permute_variant.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, i, vp, sz, vp]
+    L.moe_layer_forward_train.restype = i
+    L.moe_layer_forward_train.argtypes = [vp] * 6 + [i] * 7 + [vp, vp, vp, sz, vp]
+    L.moe_layer_backward_workspace_bytes.restype = sz
+    L.moe_layer_backward_workspace_bytes.argtypes = [i] * 6
+    L.moe_layer_backward.restype = i
+    L.moe_layer_backward.argtypes = [vp] * 7 + [i] * 7 + [vp] * 9 + [sz, vp]
     L.moe_probe_mfma_fp8.restype = i
     L.moe_probe_mfma_fp8.argtypes = [vp, i, i, vp, vp, vp]
     L.moe_probe_mfma_bf16.restype = i
@@ -361,6 +367,34 @@ def probe_mfma_bf16(image: torch.Tensor, iters: int, workgroups: int, sink: torc
                     ticks: Optional[torch.Tensor]) -> None:
     assert image.numel() * image.element_size() == 65536 and sink.numel() >= workgroups * 256
     _check(lib().moe_probe_mfma_bf16(_ptr(image), iters, workgroups, _ptr(sink), _ptr(ticks), _stream()))
+
+
+def layer_forward_train(x: torch.Tensor, w_router: torch.Tensor, logit_bias: Optional[torch.Tensor],
+                        w_gate: torch.Tensor, w_up: torch.Tensor, w_down: torch.Tensor, K: int, renormalize: bool,
+                        capacity: int, y: torch.Tensor, gu: torch.Tensor, workspace: torch.Tensor) -> None:
+    T, H = x.shape
+    E, F, _ = w_gate.shape
+    _check(lib().moe_layer_forward_train(_ptr(x), _ptr(w_router), _ptr(logit_bias), _ptr(w_gate), _ptr(w_up),
+                                         _ptr(w_down), T, H, E, K, F, int(renormalize), int(capacity), _ptr(y), _ptr(gu),
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def layer_backward_workspace_bytes(T: int, H: int, E: int, K: int, F: int, capacity: int) -> int:
+    return int(lib().moe_layer_backward_workspace_bytes(T, H, E, K, F, capacity))
+
+
+def layer_backward(x: torch.Tensor, w_router: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor,
+                   wgu_t: torch.Tensor, wd_t: torch.Tensor, dy: torch.Tensor, K: int, renormalize: bool, capacity: int,
+                   forward_workspace: torch.Tensor, gu: Optional[torch.Tensor], dx: torch.Tensor,
+                   dw_router: Optional[torch.Tensor], dbias: Optional[torch.Tensor], dw_gate: torch.Tensor,
+                   dw_up: torch.Tensor, dw_down: torch.Tensor, workspace: torch.Tensor) -> None:
+    T, H = x.shape
+    E, F, _ = w_gate.shape
+    _check(lib().moe_layer_backward(_ptr(x), _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(wgu_t), _ptr(wd_t),
+                                    _ptr(dy), T, H, E, K, F, int(renormalize), int(capacity), _ptr(forward_workspace),
+                                    _ptr(gu), _ptr(dx), _ptr(dw_router), _ptr(dbias), _ptr(dw_gate), _ptr(dw_up),
+                                    _ptr(dw_down), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                    _stream()))
 
 
 def probe_mfma_fp8(image: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor,

@@ -589,6 +589,113 @@ moe_status_t moe_layer_forward(const void* x, const void* w_router, const float*
     return moe_unpermute_combine(ws + L.y_perm, roa, gate, addend, T, H, K, L.r_max, dt, y, stream);
 }
 
+moe_status_t moe_layer_forward_train(const void* x, const void* w_router, const float* logit_bias,
+                                     const void* w_gate, const void* w_up, const void* w_down, int T,
+                                     int H, int E, int K, int F, int renormalize, int capacity, void* y,
+                                     void* gu, void* workspace, size_t workspace_bytes,
+                                     moe_stream_t stream) {
+    static const char* fn = "moe_layer_forward_train";
+    if (moe_status_t st = check_dims(fn, T, H, E, K, MOE_BF16)) return st;
+    if (F <= 0) return fail(MOE_ERR_INVALID_ARG, "%s: need F > 0", fn);
+    if (T == 0) return MOE_OK;
+    REQUIRE_PTR(fn, y);
+    REQUIRE_PTR(fn, gu);
+    const LayerLayout L = layer_layout(T, H, E, K, F, 0, capacity, MOE_BF16);
+    if (workspace == nullptr || workspace_bytes < L.total)
+        return fail(MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, L.total,
+                    workspace ? workspace_bytes : (size_t)0);
+    REQUIRE_PTR(fn, workspace);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    float* logits = reinterpret_cast<float*>(ws + L.logits);
+    int32_t* idx = reinterpret_cast<int32_t*>(ws + L.idx);
+    float* gate = reinterpret_cast<float*>(ws + L.gate);
+    int32_t* offsets = reinterpret_cast<int32_t*>(ws + L.offsets);
+    int32_t* roa = reinterpret_cast<int32_t*>(ws + L.roa);
+    moe_status_t st = moe_router_topk(x, w_router, logit_bias, logits, T, H, E, K, renormalize, MOE_BF16, idx,
+                                      gate, stream);
+    if (st) return st;
+    st = moe_permute(x, idx, T, H, E, K, capacity, MOE_BF16, ws + L.x_perm, reinterpret_cast<int32_t*>(ws + L.counts),
+                     offsets, roa, reinterpret_cast<int32_t*>(ws + L.aor), ws + L.perm_ws,
+                     permute_workspace_bytes(T, K, E), stream);
+    if (st) return st;
+    st = moe_expert_gate_up_saving(ws + L.x_perm, offsets, L.r_max, H, F, E, w_gate, w_up, ws + L.h, gu, stream);
+    if (st) return st;
+    st = moe_expert_down(ws + L.h, offsets, L.r_max, H, F, E, w_down, MOE_BF16, ws + L.y_perm, stream);
+    if (st) return st;
+    return moe_unpermute_combine(ws + L.y_perm, roa, gate, nullptr, T, H, K, L.r_max, MOE_BF16, y, stream);
+}
+
+struct LayerBackwardLayout {
+    size_t dy_perm, dx_perm, dgate, dlogits, dx_router, expert_ws, router_ws, total;
+    size_t expert_bytes, router_bytes;
+    int r_max;
+};
+
+static LayerBackwardLayout layer_backward_layout(int T, int H, int E, int K, int F, int capacity) {
+    LayerBackwardLayout L;
+    L.r_max = moe_max_rows(T, K, E, capacity);
+    const size_t R = (size_t)L.r_max;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { const size_t at = o; o = up256(o + bytes); return at; };
+    L.dy_perm = take(R * H * 2);
+    L.dx_perm = take(R * H * 2);
+    L.dgate = take((size_t)T * K * 4);
+    L.dlogits = take((size_t)T * E * 4);
+    L.dx_router = take((size_t)T * H * 2);
+    L.expert_bytes = moe_expert_backward_workspace_bytes(L.r_max, H, F, E);
+    L.expert_ws = take(L.expert_bytes);
+    L.router_bytes = router_backward_workspace_bytes(T, H, E);
+    L.router_ws = take(L.router_bytes);
+    L.total = o;
+    return L;
+}
+
+size_t moe_layer_backward_workspace_bytes(int T, int H, int E, int K, int F, int capacity) {
+    if (T < 0 || H <= 0 || E <= 0 || K <= 0 || F <= 0) return 0;
+    return layer_backward_layout(T, H, E, K, F, capacity).total;
+}
+
+moe_status_t moe_layer_backward(const void* x, const void* w_router, const void* w_gate,
+                                const void* w_up, const void* wgu_t, const void* wd_t, const void* dy,
+                                int T, int H, int E, int K, int F, int renormalize, int capacity,
+                                const void* forward_workspace, const void* gu, void* dx,
+                                float* dw_router, float* dbias, void* dw_gate, void* dw_up,
+                                void* dw_down, void* workspace, size_t workspace_bytes,
+                                moe_stream_t stream) {
+    static const char* fn = "moe_layer_backward";
+    if (moe_status_t st = check_dims(fn, T, H, E, K, MOE_BF16)) return st;
+    if (F <= 0) return fail(MOE_ERR_INVALID_ARG, "%s: need F > 0", fn);
+    REQUIRE_PTR(fn, forward_workspace);
+    REQUIRE_PTR(fn, dx);
+    const LayerLayout Lf = layer_layout(T, H, E, K, F, 0, capacity, MOE_BF16);
+    const LayerBackwardLayout L = layer_backward_layout(T, H, E, K, F, capacity);
+    if (workspace == nullptr || workspace_bytes < L.total)
+        return fail(MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, L.total,
+                    workspace ? workspace_bytes : (size_t)0);
+    REQUIRE_PTR(fn, workspace);
+    const uint8_t* fw = static_cast<const uint8_t*>(forward_workspace);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    const float* logits = reinterpret_cast<const float*>(fw + Lf.logits);
+    const int32_t* idx = reinterpret_cast<const int32_t*>(fw + Lf.idx);
+    const float* gate = reinterpret_cast<const float*>(fw + Lf.gate);
+    const int32_t* offsets = reinterpret_cast<const int32_t*>(fw + Lf.offsets);
+    const int32_t* roa = reinterpret_cast<const int32_t*>(fw + Lf.roa);
+    float* dgate = reinterpret_cast<float*>(ws + L.dgate);
+    // the forward workflow in reverse: combine, experts, router, dispatch
+    moe_status_t st = moe_unpermute_combine_backward(dy, fw + Lf.y_perm, roa, gate, T, H, K, L.r_max, MOE_BF16,
+                                                     ws + L.dy_perm, dgate, stream);
+    if (st) return st;
+    st = moe_grouped_gemm_swiglu_backward(fw + Lf.x_perm, fw + Lf.h, gu, ws + L.dy_perm, offsets, L.r_max, H, F, E,
+                                          w_gate, w_up, wgu_t, wd_t, ws + L.dx_perm, dw_gate, dw_up, dw_down,
+                                          ws + L.expert_ws, L.expert_bytes, stream);
+    if (st) return st;
+    st = moe_router_backward(x, w_router, logits, idx, dgate, T, H, E, K, renormalize, MOE_BF16,
+                             reinterpret_cast<float*>(ws + L.dlogits), ws + L.dx_router, dw_router, dbias,
+                             ws + L.router_ws, L.router_bytes, stream);
+    if (st) return st;
+    return moe_permute_backward(ws + L.dx_perm, roa, ws + L.dx_router, T, H, K, L.r_max, MOE_BF16, dx, stream);
+}
+
 float moe_fp8_delayed_scale(const float* amax_history, int len, int margin) {
     float m = 0.f;
     for (int i = 0; amax_history && i < len; ++i)

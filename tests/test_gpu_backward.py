@@ -268,3 +268,53 @@ def test_backward_of_the_whole_layer_chained_on_the_gpu(base, kw):
     _assert_grad_close(dwr.cpu().numpy(), want["dw_router"], "dw_router")
     if inp.bias is not None:
         _assert_grad_close(dbias.cpu().numpy(), want["dbias"], "dbias")
+
+
+@pytest.mark.parametrize("base,kw", [
+    ("mixtral8x22b", dict(T=640, H=256, F=384)),
+    ("tokendrop", dict(T=1536, H=256, F=256)),
+])
+def test_layer_training_step_in_two_calls(base, kw):
+    """moe_layer_forward_train + moe_layer_backward against the oracle's chain of the four backward steps."""
+    import torch
+    import paper_2504_14960_amd as moe
+    from moe_inputs import get_config, make_layer_inputs
+    from helpers import capacity_rows, guard_margins, oracle_layer_backward
+    cfg = get_config(base).scaled(**kw)
+    inp = make_layer_inputs(cfg)
+    guard_margins(inp, cfg.K)
+    capacity = capacity_rows(cfg)
+    t = inp.tensors
+    T, H, E, K, F = cfg.T, cfg.H, cfg.E, cfg.K, cfg.F
+    dy = make_tokens(cfg.seed + 5, T, H, bf16=True)
+    want = oracle_layer_backward(t["x"], t["w_router"], inp.bias, t["w_gate"], t["w_up"], t["w_down"], K,
+                                 cfg.renormalize, capacity, values(dy))
+    d = {k: to_dev(v) for k, v in t.items()}
+    bias = None if inp.bias is None else to_dev(inp.bias)
+    bf, f32 = dict(dtype=torch.bfloat16, device="cuda"), dict(dtype=torch.float32, device="cuda")
+    r_max = moe.max_rows(T, K, E, capacity)
+    fws = torch.empty(moe.layer_workspace_bytes(T, H, E, K, F, 0, capacity, moe.MOE_BF16), dtype=torch.uint8, device="cuda")
+    bws = torch.empty(moe.layer_backward_workspace_bytes(T, H, E, K, F, capacity), dtype=torch.uint8, device="cuda")
+    y, gu = torch.empty((T, H), **bf), torch.zeros((r_max, 2 * F), **bf)
+    moe.layer_forward_train(d["x"], d["w_router"], bias, d["w_gate"], d["w_up"], d["w_down"], K, cfg.renormalize,
+                            capacity, y, gu, fws)
+    y_plain = torch.empty((T, H), **bf)
+    fws2 = torch.empty_like(fws)
+    moe.layer_forward(d["x"], d["w_router"], bias, d["w_gate"], d["w_up"], d["w_down"], None, None, None, K,
+                      cfg.renormalize, capacity, y_plain, fws2)
+    wgu_t, wd_t = torch.empty((E, H, 2 * F), **bf), torch.empty((E, F, H), **bf)
+    moe.expert_weights_transpose(d["w_gate"], d["w_up"], d["w_down"], wgu_t, wd_t)
+    dx = torch.empty((T, H), **bf)
+    dwr, dbias = torch.empty((E, H), **f32), torch.empty((E,), **f32)
+    dwg, dwu, dwd = torch.empty((E, F, H), **bf), torch.empty((E, F, H), **bf), torch.empty((E, H, F), **bf)
+    moe.layer_backward(d["x"], d["w_router"], d["w_gate"], d["w_up"], wgu_t, wd_t, to_dev(dy), K, cfg.renormalize,
+                       capacity, fws, gu, dx, dwr, dbias, dwg, dwu, dwd, bws)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_plain)          # keeping g | u does not change the forward's result
+    _assert_grad_close(to_host(dx), want["dx"], "dx")
+    _assert_grad_close(to_host(dwg), want["dw_gate"], "dw_gate")
+    _assert_grad_close(to_host(dwu), want["dw_up"], "dw_up")
+    _assert_grad_close(to_host(dwd), want["dw_down"], "dw_down")
+    _assert_grad_close(dwr.cpu().numpy(), want["dw_router"], "dw_router")
+    if inp.bias is not None:
+        _assert_grad_close(dbias.cpu().numpy(), want["dbias"], "dbias")
