@@ -453,7 +453,10 @@ moe_status_t moe_probe_mfma_fp8(const void* image, int iters, int workgroups, fl
  * or 4; 0 = chosen from T and E); "wgrad_rowmajor" (1 = the expert FFN's backward
  * forms the weight gradients straight from the row-major activations with
  * transposing LDS loads instead of from transposed copies: about 1.8x slower
- * weight-gradient GEMMs, no ragged transposes; default 0). */
+ * weight-gradient GEMMs, no ragged transposes; default 0); "gemm_idle_skip" (the
+ * persistent GEMM kernels in which the waves that hold no valid row of a ragged
+ * tile skip its multiplications: 1 = always, 0 = never, -1 = for E >= 16, the
+ * default). */
 moe_status_t moe_set_option(const char* name, int value);
 
 #ifdef __cplusplus

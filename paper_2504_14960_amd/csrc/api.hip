@@ -830,6 +830,10 @@ moe_status_t moe_probe_mfma_fp8(const void* image, int iters, int workgroups, fl
 }
 
 moe_status_t moe_set_option(const char* name, int value) {
+    if (name && strcmp(name, "gemm_idle_skip") == 0) {
+        moe::set_persist_idle_skip(value < 0 ? -1 : (value != 0));
+        return MOE_OK;
+    }
     if (name && strcmp(name, "wgrad_rowmajor") == 0) {
         g_wgrad_rowmajor = value != 0;
         return MOE_OK;

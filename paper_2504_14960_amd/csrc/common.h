@@ -68,6 +68,7 @@ void launch_combine_backward(const void* dy, const void* y_perm, const int32_t* 
 
 // persistent grouped-GEMM kernels: workgroups per launch, 0 = one per compute unit
 void set_persist_workgroups(int n);
+void set_persist_idle_skip(int v);   // -1 auto, 0 off, 1 on
 
 // grouped NT GEMMs of the expert FFN.  phase bit 0: gate/up + SwiGLU (x_perm ->
 // h); bit 1: down projection (h -> y_perm).  Returns false if unsupported.

@@ -32,6 +32,7 @@ __device__ unsigned long long g_persist_ticks[1024 * 8 * 8];
 #endif
 
 static int g_persist_workgroups = 0;  // 0: one per compute unit
+static int g_persist_idle_skip = -1;  // -1: chosen from the expert count; 0 / 1: forced
 
 int persist_grid() {
     // every one of the 8 tile shares needs a workgroup with its residue mod 8
@@ -208,7 +209,7 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_r
 // features each, and lane i receives feature i of the four rows).  Both operands are read the same way, so they
 // agree on the order of the contraction values.  Rows past the expert's last one are fetched from the zero row
 // that GU points at (512 bytes of zeros).
-template <int BM, int BN, int WGM, int WGN, int MODE, bool GROUPK = false, bool KMAJ = false>
+template <int BM, int BN, int WGM, int WGN, int MODE, bool GROUPK = false, bool KMAJ = false, bool IDLE_SKIP = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, bf16_t* __restrict__ GU,
@@ -504,6 +505,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
 #ifdef MOE_PIPE_TIMING
         const unsigned long long tk_l0 = __builtin_amdgcn_s_memtime();
 #endif
+        // (IDLE_SKIP instantiations, chosen for launches with many experts, i.e. many ragged tails; the test costs
+        // the plain kernel half a per cent.)  A wave whose rows of the tile all lie past the tile's last valid row
+        // (ragged tail of an expert) has nothing to multiply: it keeps issuing its share of the loads and meeting the barriers, and leaves the
+        // matrix pipe and the LDS reads alone (under a power cap that is clock for the other workgroups).
+        const bool wave_idle = IDLE_SKIP && wm * WM >= c_rows;   // wave-uniform
+        if (!wave_idle) {
         for (int kt = 0; kt < c_kt; ++kt) {
             const Src s1 = src(kt + 1), s2 = src(kt + 2);
             const uint8_t* ca = a_region + l0;
@@ -530,6 +537,31 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
             const int te = e0;
             e0 = e1;
             e1 = te;
+        }
+        } else {
+            for (int kt = 0; kt < c_kt; ++kt) {
+                const Src s1 = src(kt + 1), s2 = src(kt + 2);
+                uint8_t* lb = b_region + e1;
+                uint8_t* la = a_region + l2;
+#pragma unroll
+                for (int i = LA; i < LC; ++i) fetch_one(i, s1, s2, lb, la);
+                __builtin_amdgcn_s_waitcnt((PA & 0xF) | ((PA >> 4) << 14));
+                __builtin_amdgcn_s_barrier();
+#pragma unroll
+                for (int i = 0; i < LA; ++i) fetch_one(i, s2, s2, b_region + e0, a_region);
+                const int tl = l0;
+                l0 = l1;
+                l1 = l2;
+                l2 = tl;
+                const int te = e0;
+                e0 = e1;
+                e1 = te;
+            }
+            // the next tile may have rows for this wave: its first fragments, as the last k-step would have read them
+            if (n_valid) {
+#pragma unroll
+                for (int q = 0; q < NREAD; ++q) read_one(a_region + l0, b_region + e0, 0, 0, q);
+            }
         }
 #ifdef MOE_PIPE_TIMING
         const unsigned long long tk_l1 = __builtin_amdgcn_s_memtime();
@@ -579,12 +611,15 @@ void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int
     constexpr int OUTN = (MODE == 1 || MODE == 2) ? BN / 2 : BN;
     constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
     const int ntn = (N + OUTN - 1) / OUTN;
-    auto kern = gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // many experts = many ragged tail tiles: the instantiation whose idle waves skip the multiplication
+    const bool idle_skip = MODE != 3 && (g_persist_idle_skip < 0 ? E >= 16 : g_persist_idle_skip != 0);
+    auto kern = idle_skip ? gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, (MODE != 3)>
+                          : gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE>;
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[idle_skip]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)smem);
-        attr_set = true;
+        attr_set[idle_skip] = true;
     }
     // never more workgroups than the static bound on the tile count
     const int grid = min(persist_grid(), grid_for(r_max, E, BM, ntn));
@@ -655,6 +690,7 @@ void run_persist_pair(const void* x_perm, const int32_t* offsets, int r_max, int
 }  // namespace
 
 void set_persist_workgroups(int n) { g_persist_workgroups = n; }
+void set_persist_idle_skip(int v) { g_persist_idle_skip = v; }
 
 // C [rows, N] = A [rows, K] . B[e]^T with B [E, N, K], rows grouped by expert (bf16): the
 // down-projection form of the persistent kernel, for any operands of that shape

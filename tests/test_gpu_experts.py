@@ -98,6 +98,21 @@ def test_persistent_kernel_walks_many_tiles_per_workgroup(ragged_case, variant, 
     assert_close(y, y_ref, True, f"y_perm (variant {variant}, {workgroups} workgroups)")
 
 
+@pytest.mark.parametrize("variant", [40, 41])
+@pytest.mark.parametrize("idle_skip", [0, 1])
+def test_waves_without_valid_rows_may_skip_their_multiplications(variant, idle_skip):
+    # experts whose last tile holds at most 128 rows (half of the waves idle), exactly 128, one row, and full tiles
+    import paper_2504_14960_amd as moe
+    inp, x_perm, offsets, h_ref, y_ref = _case(H=256, F=384, E=7, counts=[300, 128, 1, 513, 0, 256, 90], seed=4500)
+    moe.set_option("gemm_idle_skip", idle_skip)
+    try:
+        h, y = _run(x_perm, offsets, inp, variant)
+    finally:
+        moe.set_option("gemm_idle_skip", -1)
+    assert_close(h, h_ref, True, f"h (variant {variant}, idle_skip {idle_skip})")
+    assert_close(y, y_ref, True, f"y_perm (variant {variant}, idle_skip {idle_skip})")
+
+
 def test_rows_past_the_last_expert_are_untouched_and_result_is_reproducible():
     inp, x_perm, offsets, h_ref, y_ref = _case(H=128, F=256, E=4, counts=[100, 50, 0, 270], seed=4300, r_pad=37)
     R = int(offsets[-1])
