@@ -9,6 +9,8 @@ namespace moe {
 // workgroups a persistent grouped-GEMM kernel is launched with: one per compute
 // unit unless overridden (at least 8, one per tile share)
 int persist_grid();
+// whether a launch over E experts uses the kernels whose waves without valid rows skip the multiplications
+bool persist_idle_skip(int E);
 
 namespace {
 

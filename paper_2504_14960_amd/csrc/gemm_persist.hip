@@ -612,7 +612,7 @@ void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int
     constexpr size_t smem = (size_t)(3 * BM + 2 * BN) * 64 * 2;
     const int ntn = (N + OUTN - 1) / OUTN;
     // many experts = many ragged tail tiles: the instantiation whose idle waves skip the multiplication
-    const bool idle_skip = MODE != 3 && (g_persist_idle_skip < 0 ? E >= 16 : g_persist_idle_skip != 0);
+    const bool idle_skip = MODE != 3 && persist_idle_skip(E);
     auto kern = idle_skip ? gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, (MODE != 3)>
                           : gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE>;
     static bool attr_set[2] = {false, false};
@@ -691,6 +691,7 @@ void run_persist_pair(const void* x_perm, const int32_t* offsets, int r_max, int
 
 void set_persist_workgroups(int n) { g_persist_workgroups = n; }
 void set_persist_idle_skip(int v) { g_persist_idle_skip = v; }
+bool persist_idle_skip(int E) { return g_persist_idle_skip < 0 ? E >= 16 : g_persist_idle_skip != 0; }
 
 // C [rows, N] = A [rows, K] . B[e]^T with B [E, N, K], rows grouped by expert (bf16): the
 // down-projection form of the persistent kernel, for any operands of that shape

@@ -128,7 +128,7 @@ __device__ __forceinline__ void store_y_bf16(f32x16 (&acc)[FM][FN], int t_row0, 
 // A [rows, K] E4M3, B0/B1 [E, N, K] E4M3 (SWIGLU: gate and up), K a multiple of
 // 128.  SWIGLU: C is h [rows, N] E4M3, s0/s1 dequantise g/u, s2 scales h, amax
 // receives max |h|.  Otherwise C is y [rows, N] bf16 and s0 dequantises it.
-template <bool SWIGLU>
+template <bool SWIGLU, bool IDLE_SKIP = false>
 __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
     const uint8_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const uint8_t* __restrict__ B0, const uint8_t* __restrict__ B1, void* __restrict__ C, int ntn, float s0,
@@ -327,6 +327,10 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
     int l0 = 0, l1 = A_BYTES, l2 = 2 * A_BYTES;
     int e0 = 0, e1 = B_BYTES;
     for (;;) {
+        // IDLE_SKIP (launches with many experts): a wave whose rows of the tile all lie past its last valid row
+        // only issues its share of the loads and meets the barriers (see gemm_persist.hip)
+        const bool wave_idle = IDLE_SKIP && wm * WM >= c_rows;   // wave-uniform
+        if (!wave_idle) {
         for (int kt = 0; kt < KT; ++kt) {
             const Src q1 = src(kt + 1), q2 = src(kt + 2);
             __builtin_amdgcn_sched_barrier(0);
@@ -346,6 +350,28 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
             const int te = e0;
             e0 = e1;
             e1 = te;
+        }
+        } else {
+            for (int kt = 0; kt < KT; ++kt) {
+                const Src q1 = src(kt + 1), q2 = src(kt + 2);
+#pragma unroll
+                for (int i = LA; i < NLOAD; ++i) fetch_one(i, q1, q2, b_region + e1, a_region + l2);
+                __builtin_amdgcn_s_waitcnt((PA & 0xF) | ((PA >> 4) << 14));
+                __builtin_amdgcn_s_barrier();
+#pragma unroll
+                for (int i = 0; i < LA; ++i) fetch_one(i, q2, q2, b_region + e0, a_region);
+                const int tl = l0;
+                l0 = l1;
+                l1 = l2;
+                l2 = tl;
+                const int te = e0;
+                e0 = e1;
+                e1 = te;
+            }
+            if (n_valid) {   // the next tile may have rows for this wave: its first fragments
+#pragma unroll
+                for (int r = 0; r < NREAD; ++r) read_one(a_region + l0, b_region + e0, 0, 0, r);
+            }
         }
         uint8_t* stage = a_region + l2 + wave * (32 * FN * 64);
         if (SWIGLU)
@@ -385,12 +411,14 @@ void launch_fp8(const void* A, const int32_t* offsets, int r_max, int E, int N, 
     constexpr int OUTN = SWIGLU ? 128 : 256;
     constexpr size_t smem = (size_t)(3 * 256 + 2 * 256) * 128;
     const int ntn = (N + OUTN - 1) / OUTN;
-    auto kern = gemm_fp8_persist_kernel<SWIGLU>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // (the gate/up kernel has no registers to spare for the second loop: down projection only)
+    const bool idle_skip = !SWIGLU && persist_idle_skip(E);
+    auto kern = idle_skip ? gemm_fp8_persist_kernel<SWIGLU, !SWIGLU> : gemm_fp8_persist_kernel<SWIGLU, false>;
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[idle_skip]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)smem);
-        attr_set = true;
+        attr_set[idle_skip] = true;
     }
     const int grid = min(persist_grid(), grid_for(r_max, E, 256, ntn));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, static_cast<const uint8_t*>(A), offsets, E, N, K,
