@@ -101,6 +101,8 @@ __global__ __launch_bounds__(256) void permute_map_kernel(
     }
 
     // rank of every assignment of this chunk inside its (expert, 64-assignment unit)
+    int nbits = 0;
+    while ((1 << nbits) < E) ++nbits;
     int my_e[kChunk / 256], my_r[kChunk / 256];
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
@@ -110,15 +112,17 @@ __global__ __launch_bounds__(256) void permute_map_kernel(
         int e = (a < A) ? idx[a] : -1;
         const bool valid = (unsigned)e < (unsigned)E;
         if (!valid) e = -1;
+        // lanes of this unit that name the same expert: one ballot per bit of the expert index
+        uint64_t peers = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {   // uniform trip count
+            const bool bit = (e >> b) & 1;
+            const uint64_t m = __ballot(valid && bit);
+            peers &= bit ? m : ~m;
+        }
         int r = 0;
-        uint64_t remaining = __ballot(valid);
-        while (remaining) {
-            const int leader = __ffsll((unsigned long long)remaining) - 1;
-            const int e0 = __shfl(e, leader, 64);
-            const uint64_t mask = __ballot(e == e0);
-            if (e == e0) r = __popcll(mask & lt_mask);
-            if (lane == leader) unit_cnt[u][e0] = __popcll(mask);
-            remaining &= ~mask;
+        if (valid) {
+            r = __popcll(peers & lt_mask);
+            if (r == 0) unit_cnt[u][e] = __popcll(peers);   // the first lane of the group records its size
         }
         my_e[j] = e;
         my_r[j] = r;
