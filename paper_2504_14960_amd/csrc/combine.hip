@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void combine_small_k_kernel(
     const float* __restrict__ gate, const uint8_t* __restrict__ addend, uint8_t* __restrict__ y, int T,
     int K, int row_bytes, int r_max) {
     constexpr int NV = BF16 ? 8 : 4;
-    constexpr int CP = 8 / KMAX;  // 1 KiB slices per pass
+    constexpr int CP = KMAX == 8 ? 2 : 8 / KMAX;  // 1 KiB slices per pass (8 to 16 loads per lane in flight)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int t = blockIdx.x * 4 + wave; t < T; t += gridDim.x * 4) {
         int my_row = -1;
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256) void combine_backward_small_k_kernel(
     const float* __restrict__ gate, uint8_t* __restrict__ dy_perm, float* __restrict__ dgate, int T, int K,
     int row_bytes, int r_max) {
     constexpr int NV = BF16 ? 8 : 4;
-    constexpr int CP = 8 / KMAX;  // 1 KiB slices per pass
+    constexpr int CP = KMAX == 8 ? 2 : 8 / KMAX;  // 1 KiB slices per pass (8 to 16 loads per lane in flight)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int t = blockIdx.x * 4 + wave; t < T; t += gridDim.x * 4) {
         int my_row = -1;
