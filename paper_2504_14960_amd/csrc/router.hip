@@ -306,7 +306,12 @@ __global__ __launch_bounds__(256) void router_bf16_kernel(
         }
     };
 
-    if (wave < nchunks) load_chunk(wave);
+    // workgroups start at different slices of the hidden dimension: the rows of x
+    // and of the router weight lie a whole row apart, so workgroups that walk the
+    // slices in step would all ask the same few memory channels at a time
+    const int rot = (int)((blockIdx.x * 7u) % (unsigned)nchunks);
+    auto slice_of = [&](int c) { const int cc = c + rot; return cc >= nchunks ? cc - nchunks : cc; };
+    if (wave < nchunks) load_chunk(slice_of(wave));
     for (int c = wave; c < nchunks; c += 4) {
         bf16x8 bfrag[KSTEPS][NB];
 #pragma unroll
@@ -316,7 +321,7 @@ __global__ __launch_bounds__(256) void router_bf16_kernel(
         for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
             for (int b2 = 0; b2 < NB; ++b2) bfrag[s][b2] = __builtin_bit_cast(bf16x8, wr[s][b2]);
-        if (c + 4 < nchunks) load_chunk(c + 4);
+        if (c + 4 < nchunks) load_chunk(slice_of(c + 4));
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -459,10 +464,10 @@ void launch_router(const void* x, const void* w, const float* bias, float* logit
         return;
     }
     const int nb = (E + 15) / 16;
-    // tokens per workgroup: enough workgroups to fill 256 CUs, but for many
-    // experts a taller tile so the router weight is re-read less often
+    // tokens per workgroup: enough workgroups to fill 256 CUs, but from 16
+    // experts on a taller tile so the router weight is re-read less often
     int mb = (T >= 32768) ? 4 : (T >= 16384 ? 2 : 1);
-    if (nb >= 4 && mb < 2) mb = 2;
+    if (E >= 16 && mb < 2) mb = 2;
     if (g_router_tile == 1 || g_router_tile == 2 || g_router_tile == 4) mb = g_router_tile;
 #define ROUTER_CASE(M, N)                                                          \
     launch_bf16<M, N>(x, w, bias, logits, T, H, E, K, renorm, idx, gate, s);       \
