@@ -31,6 +31,7 @@ def lib() -> C.CDLL:
         L.oracle_permute.restype = C.c_int
         L.oracle_permute_variant.restype = C.c_int
         L.oracle_layer_forward.restype = C.c_int
+        L.oracle_sort_chunks.restype = C.c_longlong
         L.oracle_fp8_decode.restype = C.c_double
         L.oracle_fp8_decode.argtypes = [C.c_uint8]
         L.oracle_fp8_encode.restype = C.c_uint8
@@ -278,6 +279,30 @@ def permute_backward(dx_perm: np.ndarray, row_of_assign: np.ndarray, T: int, K: 
     dx = np.zeros((T, H), dtype=np.float64)
     lib().oracle_permute_backward(_p(dx_perm), _p(roa), _p(addend), T, H, K, _p(dx))
     return dx
+
+
+def sort_chunks(src: Optional[np.ndarray], chunk_rows, order, group: int = 0, r_dst: Optional[int] = None):
+    """Gather of ragged row chunks: dst = chunks order[0], order[1], ... of src.
+
+    Returns (dst [r_dst, H] or None, rows of each dst chunk, group offsets or None, total rows)."""
+    chunk_rows = np.ascontiguousarray(chunk_rows, dtype=np.int32).reshape(-1)
+    order = np.ascontiguousarray(order, dtype=np.int32).reshape(-1)
+    n_src, n_dst = chunk_rows.size, order.size
+    rows_out = np.zeros(n_dst, dtype=np.int32)
+    goff = np.zeros((n_dst + group - 1) // group + 1, dtype=np.int32) if group > 0 else None
+    if src is not None:
+        src = np.ascontiguousarray(src)
+        r_src, row_bytes = src.shape[0], src.shape[1] * src.itemsize
+    else:
+        r_src, row_bytes = 0, 0
+    if r_dst is None:
+        valid = (order >= 0) & (order < n_src)
+        r_dst = int(np.maximum(chunk_rows, 0)[order[valid]].sum())
+    dst = np.zeros((r_dst, src.shape[1]), dtype=src.dtype) if src is not None else None
+    total = lib().oracle_sort_chunks(_p(src), C.c_longlong(r_src), _p(chunk_rows), n_src, _p(order), n_dst,
+                                     int(group), C.c_size_t(row_bytes), _p(dst), C.c_longlong(r_dst),
+                                     _p(rows_out), _p(goff))
+    return dst, rows_out, goff, int(total)
 
 
 class LayerResult:

@@ -45,7 +45,9 @@
  * experts give permute/unpermute round trip, brute-force dense Eq. 1 below,
  * batch-split invariance, dropped-tokens-are-zero; the two backward functions by
  * the adjoint identity <F(a), b> = <a, F'(b)> on random tensors, finite
- * differences in the gates, and a library scatter-add.  No function here is
+ * differences in the gates, and a library scatter-add; the chunk gather by
+ * numpy split/concatenate, its inverse, and by a simulated expert-parallel
+ * group whose output must equal the one-GPU layer's.  No function here is
  * "parity unpinned"; the paper prints no worked numeric example of the layer.
  */
 #include <math.h>
@@ -550,6 +552,43 @@ void oracle_permute_backward(const double* dx_perm, const int32_t* row_of_assign
             if (addend) acc += addend[(size_t)t * H + n];
             dx[(size_t)t * H + n] = acc;
         }
+}
+
+/* ---- expert-parallel share of one GPU: received rows by source, needed by expert ----
+ * Section 3.3, forward workflow: after the All-to-All-V over the EP group a GPU
+ * holds, for every source rank in turn, that rank's rows for each of the local
+ * experts; the expert computation needs all rows of one expert together, and the
+ * way back needs the source order again.  The paper names no operation for this;
+ * the reading here is a gather of row chunks: src is a sequence of n_src chunks,
+ * chunk c having chunk_rows[c] rows (negative counts as 0); dst is the sequence
+ * of chunks order[0], order[1], ... (a chunk named twice is copied twice, an index
+ * outside [0, n_src) stands for an empty chunk).  A row is copied when it lies
+ * below r_src in src and below r_dst in dst.  chunk_rows_out[p] = rows of dst
+ * chunk p; group_offsets[g] = first dst row of chunk g*group (group > 0), with
+ * one more entry for the total.  Returns the total number of dst rows. */
+long long oracle_sort_chunks(const void* src, long long r_src, const int32_t* chunk_rows, int n_src,
+                             const int32_t* order, int n_dst, int group, size_t row_bytes,
+                             void* dst, long long r_dst, int32_t* chunk_rows_out,
+                             int32_t* group_offsets) {
+    long long* src_start = (long long*)malloc(sizeof(long long) * (size_t)(n_src + 1));
+    src_start[0] = 0;
+    for (int c = 0; c < n_src; ++c) src_start[c + 1] = src_start[c] + (chunk_rows[c] > 0 ? chunk_rows[c] : 0);
+    long long d = 0;
+    for (int p = 0; p < n_dst; ++p) {
+        if (group_offsets && group > 0 && p % group == 0) group_offsets[p / group] = (int32_t)d;
+        const int c = order[p];
+        const long long n = (c >= 0 && c < n_src) ? src_start[c + 1] - src_start[c] : 0;
+        if (chunk_rows_out) chunk_rows_out[p] = (int32_t)n;
+        for (long long i = 0; i < n; ++i) {
+            const long long from = src_start[c] + i, to = d + i;
+            if (src && dst && from < r_src && to < r_dst)
+                memcpy((char*)dst + (size_t)to * row_bytes, (const char*)src + (size_t)from * row_bytes, row_bytes);
+        }
+        d += n;
+    }
+    if (group_offsets && group > 0) group_offsets[(n_dst + group - 1) / group] = (int32_t)d;
+    free(src_start);
+    return d;
 }
 
 /* ---- the whole layer through the dispatcher's data path ----

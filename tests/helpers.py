@@ -103,3 +103,47 @@ def oracle_layer_backward(x, w_router, bias, w_gate, w_up, w_down, K, renorm, ca
     dl, dx_r, dw_r, db = oracle.router_backward(x, w_router, logits32, idx, dgate, renorm)
     dx = oracle.permute_backward(dx_perm if R else np.zeros((1, H)), perm.row_of_assign, T, K, addend=dx_r)
     return dict(dx=dx, dw_router=dw_r, dbias=db, dw_gate=dwg, dw_up=dwu, dw_down=dwd, idx=idx)
+
+
+def ep_chunk_orders(S: int, El: int):
+    """Chunk orders of one GPU of an expert-parallel group of S ranks with El local experts: received chunks lie
+    source-major (chunk s*El+e); `by_expert` lists them expert-major, `by_source` is the way back."""
+    by_expert = np.array([s * El + e for e in range(El) for s in range(S)], dtype=np.int32)
+    by_source = np.array([e * S + s for s in range(S) for e in range(El)], dtype=np.int32)
+    return by_expert, by_source
+
+
+def oracle_ep_group_forward(xs, w_router, bias, w_gate, w_up, w_down, K, renorm, capacity=0):
+    """The layer over an expert-parallel group simulated on the CPU with the oracle's pieces (Section 3.3 forward
+    workflow): every rank routes and permutes its own tokens, the All-to-All-V is a slicing of host arrays, each
+    rank gathers what it received by expert (oracle.sort_chunks), runs its local experts, gathers back by source,
+    the second All-to-All-V returns the rows, and every rank combines.  Returns one y [T_s, H] (double) per rank."""
+    S = len(xs)
+    E = w_gate.shape[0]
+    assert E % S == 0
+    El = E // S
+    perms, gates = [], []
+    for x in xs:
+        logits32 = oracle.router_logits(x, w_router, bias).astype(np.float32)
+        idx, gate = oracle.topk_gates(logits32, K, renorm)
+        perms.append(oracle.permute(x, idx, E, capacity))
+        gates.append(gate)
+    by_expert, by_source = ep_chunk_orders(S, El)
+    returned = [[None] * S for _ in range(S)]          # returned[s][d]: rows rank s gets back from rank d
+    for d in range(S):
+        lo, hi = d * El, (d + 1) * El
+        recv = np.concatenate([p.x_perm[p.offsets[lo]:p.offsets[hi]] for p in perms])
+        chunk_rows = np.concatenate([p.counts[lo:hi] for p in perms])
+        grouped, rows_by_expert, goff, total = oracle.sort_chunks(recv, chunk_rows, by_expert, group=S)
+        assert total == recv.shape[0]
+        y_rows = oracle.experts(grouped, goff, w_gate[lo:hi], w_up[lo:hi], w_down[lo:hi])
+        back, rows_by_source, _, _ = oracle.sort_chunks(y_rows, rows_by_expert, by_source)
+        np.testing.assert_array_equal(rows_by_source, chunk_rows)
+        bounds = np.concatenate([[0], np.cumsum([p.offsets[hi] - p.offsets[lo] for p in perms])])
+        for s in range(S):
+            returned[s][d] = back[bounds[s]:bounds[s + 1]]
+    ys = []
+    for s in range(S):
+        y_perm = np.concatenate(returned[s])
+        ys.append(oracle.combine(y_perm, perms[s].row_of_assign, gates[s]))
+    return ys

@@ -72,6 +72,13 @@ MUTANTS = [
      ["test_oracle_fp8.py"]),
     ("fp8: encode saturates one code early", "moe_oracle_fp8.c", "if (a > 448.0) return (uint8_t)(sign | 0x7e);", "if (a > 416.0) return (uint8_t)(sign | 0x7e);",
      ["test_oracle_fp8.py"]),
+    ("chunk gather: source chunks start one chunk late", "moe_oracle.c", "const long long from = src_start[c] + i, to = d + i;",
+     "const long long from = src_start[c + 1] + i, to = d + i;", ["test_oracle_sort_chunks.py"]),
+    ("chunk gather: destination chunk takes the size of its own position", "moe_oracle.c",
+     "const long long n = (c >= 0 && c < n_src) ? src_start[c + 1] - src_start[c] : 0;",
+     "const long long n = (c >= 0 && c < n_src && p < n_src) ? src_start[p + 1] - src_start[p] : 0;", ["test_oracle_sort_chunks.py"]),
+    ("chunk gather: group offsets one chunk early", "moe_oracle.c", "if (group_offsets && group > 0 && p % group == 0) group_offsets[p / group] = (int32_t)d;",
+     "if (group_offsets && group > 0 && (p + 1) % group == 0) group_offsets[p / group] = (int32_t)d;", ["test_oracle_sort_chunks.py"]),
 ]
 
 
