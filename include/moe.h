@@ -155,6 +155,44 @@ moe_status_t moe_permute_variant(const void* x, const int32_t* topk_idx, const f
                                  void* workspace, size_t workspace_bytes, moe_stream_t stream);
 
 /*
+ * One GPU's step of expert-parallel dispatch (Section 3.3, forward workflow:
+ * permute, All-to-All-V over the EP group, expert computation, All-to-All-V
+ * back, un-permute).  After the first All-to-All-V a GPU that owns several
+ * experts holds, source rank by source rank, each source's rows for its local
+ * experts in turn; the grouped GEMM needs all rows of an expert together, and
+ * the second All-to-All-V needs the source order again.  Both are this gather
+ * of row chunks (the paper does not name the operation; the collective itself
+ * is not part of this library):
+ *
+ *   src [R_src,H] (dt) is a sequence of n_src chunks, chunk c having
+ *   chunk_rows[c] rows (int32 [n_src], DEVICE memory; negative counts as 0).
+ *   dst [R_dst,H] receives the chunks order[0], order[1], ..., order[n_dst-1]
+ *   (int32 [n_dst], DEVICE memory) one after the other.  A chunk named twice is
+ *   copied twice; an index outside [0, n_src) stands for an empty chunk.  A row
+ *   is copied when it lies below R_src in src and below R_dst in dst; all other
+ *   rows of dst are left untouched.  src and dst must not overlap; either may
+ *   be NULL (then only the outputs below are written).
+ *
+ *   chunk_rows_out [n_dst] (optional): rows of every destination chunk, i.e. the
+ *   chunk_rows of the way back.  group_offsets [ceil(n_dst/group) + 1]
+ *   (optional, needs group > 0): first dst row of chunk g*group, and the total
+ *   as last entry -- with the received chunks listed expert-major and group =
+ *   number of source ranks this is the expert_offsets array of a3.
+ *
+ * For S source ranks and L local experts the received chunk (s, e) is chunk
+ * s*L + e of src; order[e*S + s] = s*L + e gathers by expert, and on the way
+ * back order[s*L + e] = e*S + s with chunk_rows = the first call's
+ * chunk_rows_out.  n_src, n_dst <= 4096.  Rows are opaque: any payload with
+ * H * sizeof(dt) bytes per row, a multiple of 16.  workspace:
+ * moe_sort_chunks_workspace_bytes(n_dst) bytes of device memory.
+ */
+size_t moe_sort_chunks_workspace_bytes(int n_dst);
+moe_status_t moe_sort_chunks(const void* src, int R_src, const int32_t* chunk_rows, int n_src,
+                             const int32_t* order, int n_dst, int group, int H, moe_dtype_t dt,
+                             void* dst, int R_dst, int32_t* chunk_rows_out, int32_t* group_offsets,
+                             void* workspace, size_t workspace_bytes, moe_stream_t stream);
+
+/*
  * a3. Experts: Section 3.1.2 "Expert Computation"; f_e of Eq. 1 as a bias-free
  * SwiGLU FFN (the paper leaves f_e open):
  *

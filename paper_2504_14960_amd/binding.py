@@ -80,6 +80,10 @@ def lib() -> C.CDLL:
     L.moe_grouped_gemm_swiglu_backward.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.moe_permute_variant_workspace_bytes.restype = sz
     L.moe_permute_variant_workspace_bytes.argtypes = [i, i, i]
+    L.moe_sort_chunks_workspace_bytes.restype = sz
+    L.moe_sort_chunks_workspace_bytes.argtypes = [i]
+    L.moe_sort_chunks.restype = i
+    L.moe_sort_chunks.argtypes = [vp, i, vp, i, vp, i, i, i, i, vp, i, vp, vp, vp, sz, vp]
     L.moe_permute_variant.restype = i
     L.moe_permute_variant.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, i, vp, sz, vp]
     L.moe_layer_forward_train.restype = i
@@ -361,6 +365,24 @@ def permute_variant(x: Optional[torch.Tensor], topk_idx: torch.Tensor, scores: O
                                      _ptr(x_perm), _ptr(expert_counts), _ptr(expert_offsets), _ptr(row_of_assign),
                                      _ptr(assign_of_row), assign_of_row.numel(), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sort_chunks_workspace_bytes(n_dst: int) -> int:
+    return int(lib().moe_sort_chunks_workspace_bytes(n_dst))
+
+
+def sort_chunks(src: Optional[torch.Tensor], chunk_rows: torch.Tensor, order: torch.Tensor, group: int,
+                dst: Optional[torch.Tensor], chunk_rows_out: Optional[torch.Tensor],
+                group_offsets: Optional[torch.Tensor], workspace: torch.Tensor, H: Optional[int] = None,
+                dtype: Optional[int] = None) -> None:
+    ref = src if src is not None else dst
+    if ref is not None:
+        H, dtype = ref.shape[1], _dt(ref)
+    _check(lib().moe_sort_chunks(_ptr(src), 0 if src is None else src.shape[0], _ptr(chunk_rows), chunk_rows.numel(),
+                                 _ptr(order), order.numel(), group, H or 8, MOE_BF16 if dtype is None else dtype,
+                                 _ptr(dst), 0 if dst is None else dst.shape[0], _ptr(chunk_rows_out),
+                                 _ptr(group_offsets), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream()))
 
 
 def probe_mfma_bf16(image: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor,

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe_hip.so")
-SOURCES = ["api.hip", "router.hip", "permute.hip", "combine.hip", "grouped_gemm.hip", "gemm_pipe3.hip", "gemm_persist.hip", "gemm_persist_fp8.hip", "fp8_quant.hip", "ffn_backward.hip", "router_backward.hip", "probe.hip"]
+SOURCES = ["api.hip", "router.hip", "permute.hip", "combine.hip", "grouped_gemm.hip", "gemm_pipe3.hip", "gemm_persist.hip", "gemm_persist_fp8.hip", "fp8_quant.hip", "ffn_backward.hip", "router_backward.hip", "probe.hip", "chunks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -217,6 +217,44 @@ moe_status_t moe_permute_variant(const void* x, const int32_t* topk_idx, const f
     return check_launch(fn);
 }
 
+size_t moe_sort_chunks_workspace_bytes(int n_dst) {
+    if (n_dst < 0 || n_dst > sort_chunks_max_chunks()) return 0;
+    return sort_chunks_workspace_bytes(n_dst);
+}
+
+moe_status_t moe_sort_chunks(const void* src, int R_src, const int32_t* chunk_rows, int n_src,
+                             const int32_t* order, int n_dst, int group, int H, moe_dtype_t dt,
+                             void* dst, int R_dst, int32_t* chunk_rows_out, int32_t* group_offsets,
+                             void* workspace, size_t workspace_bytes, moe_stream_t stream) {
+    static const char* fn = "moe_sort_chunks";
+    if (dt != MOE_F32 && dt != MOE_BF16) return fail(MOE_ERR_INVALID_ARG, "%s: unknown dtype %d", fn, (int)dt);
+    if (R_src < 0 || R_dst < 0 || n_src < 0 || n_dst < 0 || H <= 0 || group < 0)
+        return fail(MOE_ERR_INVALID_ARG, "%s: need R_src, R_dst, n_src, n_dst, group >= 0 and H > 0", fn);
+    if (n_src > sort_chunks_max_chunks() || n_dst > sort_chunks_max_chunks())
+        return fail(MOE_ERR_UNSUPPORTED, "%s: n_src=%d, n_dst=%d exceed the limit %d", fn, n_src, n_dst,
+                    sort_chunks_max_chunks());
+    const long long row_bytes = (long long)H * (dt == MOE_BF16 ? 2 : 4);
+    if (row_bytes % 16 || row_bytes > INT32_MAX)
+        return fail(MOE_ERR_UNSUPPORTED, "%s: a row of %lld bytes is not a multiple of 16", fn, row_bytes);
+    if (group_offsets != nullptr && group <= 0)
+        return fail(MOE_ERR_INVALID_ARG, "%s: group_offsets needs group > 0", fn);
+    if (n_src > 0) REQUIRE_PTR(fn, chunk_rows);
+    if (n_dst > 0) REQUIRE_PTR(fn, order);
+    if (src != nullptr && dst != nullptr && R_src > 0 && R_dst > 0) {
+        const char* a = static_cast<const char*>(src);
+        const char* b = static_cast<const char*>(dst);
+        if (a < b + (size_t)R_dst * row_bytes && b < a + (size_t)R_src * row_bytes)
+            return fail(MOE_ERR_INVALID_ARG, "%s: src and dst overlap", fn);
+    }
+    const size_t need = sort_chunks_workspace_bytes(n_dst);
+    if (workspace == nullptr || workspace_bytes < need)
+        return fail(MOE_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need,
+                    workspace ? workspace_bytes : (size_t)0);
+    launch_sort_chunks(src, R_src, chunk_rows, n_src, order, n_dst, group_offsets ? group : 0, (int)row_bytes, dst,
+                       R_dst, chunk_rows_out, group_offsets, workspace, static_cast<hipStream_t>(stream));
+    return check_launch(fn);
+}
+
 static moe_status_t expert_ffn(const char* fn, int phase, const void* x_perm,
                                const int32_t* expert_offsets, int R_max, int H, int F, int E,
                                const void* w_gate, const void* w_up, const void* w_down,

@@ -89,6 +89,13 @@ void launch_permute_zero_rows(const int32_t* assign_of_row, void* x_perm, int ro
 
 void launch_fill_i32(int32_t* p, int n, int32_t v0, int32_t step, hipStream_t s);
 
+// gather of ragged row chunks (expert-parallel share of one GPU): dst = src chunks order[0], order[1], ...
+int sort_chunks_max_chunks();
+size_t sort_chunks_workspace_bytes(int n_dst);
+void launch_sort_chunks(const void* src, int r_src, const int32_t* chunk_rows, int n_src, const int32_t* order,
+                        int n_dst, int group, int row_bytes, void* dst, int r_dst, int32_t* chunk_rows_out,
+                        int32_t* group_offsets, void* ws, hipStream_t s);
+
 // ---- pieces of the expert FFN's backward (bf16) ----
 // C [rows, N] = A [rows, K] . B[e]^T, B [E, N, K], rows grouped by expert; false if the shape is not covered
 bool launch_grouped_nt(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B,
