@@ -56,6 +56,10 @@ def parse_args():
     ap.add_argument("--permute-variants", action="store_true",
                     help="also time moe_permute_variant (drop by score, pad to capacity) on the same routing; "
                          "workloads with a capacity factor only")
+    ap.add_argument("--ep-share", type=int, default=0, metavar="S",
+                    help="also time what ONE GPU of an S-rank expert-parallel group of this workload does between the "
+                         "two All-to-All-Vs: gather the received chunks by expert, run its E/S experts, gather back "
+                         "by source (every rank holding this workload's token count; no collective is run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the bare-MFMA probe (what this box sustains on zero and on workload-like operands)")
@@ -488,6 +492,68 @@ def main():
                        "frac": round(work / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
         step(s0)      # leave the plain dispatch's maps behind for what follows
         out["permute_variants"] = res
+    if args.ep_share:
+        S = args.ep_share
+        if E % S or fp8 or not bf16:
+            print("bench.py: --ep-share S needs a bf16 workload (not --precision fp8) with E divisible by S", file=sys.stderr)
+            sys.exit(2)
+        El = E // S
+        step(sets[0])
+        cnt = sets[0]["counts"].cpu().numpy()
+        loads = cnt.reshape(S, El).sum(1)
+        d = int(loads.argmax())                          # the rank the group waits for
+        # every source sends what this batch sends: i.i.d. batches differ by a few per cent only
+        chunk = np.tile(cnt[d * El:(d + 1) * El], S).astype(np.int32)          # chunk (s, e), source-major
+        Rr = int(chunk.sum())
+        by_expert = np.array([sr * El + e for e in range(El) for sr in range(S)], dtype=np.int32)
+        by_source = np.array([e * S + sr for sr in range(S) for e in range(El)], dtype=np.int32)
+        g = dict(recv=torch.randn((Rr, H), dtype=tdt, device="cuda"),
+                 grouped=torch.empty((Rr, H), dtype=tdt, device="cuda"),
+                 h=torch.empty((Rr, F), dtype=tdt, device="cuda"),
+                 y=torch.empty((Rr, H), dtype=tdt, device="cuda"),
+                 back=torch.empty((Rr, H), dtype=tdt, device="cuda"),
+                 chunk=torch.from_numpy(chunk).cuda(), by_expert=torch.from_numpy(by_expert).cuda(),
+                 by_source=torch.from_numpy(by_source).cuda(),
+                 rows_e=torch.empty(S * El, dtype=torch.int32, device="cuda"),
+                 goff=torch.empty(El + 1, dtype=torch.int32, device="cuda"),
+                 ws=torch.empty(moe.sort_chunks_workspace_bytes(S * El) + 256, dtype=torch.uint8, device="cuda"))
+        wl = {k: w[k][d * El:(d + 1) * El] for k in ("w_gate", "w_up", "w_down")}
+        enames = ["gather_by_expert", "gate_up", "down", "gather_by_source"]
+        def estep(ev=None):
+            def mark(i):
+                if ev is not None:
+                    ev[i].record()
+            mark(0)
+            moe.sort_chunks(g["recv"], g["chunk"], g["by_expert"], S, g["grouped"], g["rows_e"], g["goff"], g["ws"])
+            mark(1)
+            moe.expert_gate_up(g["grouped"], g["goff"], wl["w_gate"], wl["w_up"], g["h"])
+            mark(2)
+            moe.expert_down(g["h"], g["goff"], wl["w_down"], g["y"])
+            mark(3)
+            moe.sort_chunks(g["y"], g["rows_e"], g["by_source"], 0, g["back"], None, None, g["ws"])
+            mark(4)
+        for _ in range(max(2, args.warmup)):
+            estep()
+        n_e = max(3, args.steps)
+        eev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(n_e)]
+        torch.cuda.synchronize()
+        te0 = time.perf_counter()
+        for i in range(n_e):
+            estep(eev[i])
+        torch.cuda.synchronize()
+        ems = (time.perf_counter() - te0) * 1e3 / n_e
+        est = {nm: round(sum(eev[i][j].elapsed_time(eev[i][j + 1]) for i in range(n_e)) / n_e, 4)
+               for j, nm in enumerate(enames)}
+        gbytes = 2.0 * Rr * H * es                      # every row read once and written once
+        gms = 0.5 * (est["gather_by_expert"] + est["gather_by_source"])
+        out["ep_share"] = {
+            "ranks": S, "local_experts": El, "rank": d, "rows_received": Rr, "mean_rows_per_rank": round(float(loads.mean()) * S, 1),
+            "chunks": S * El, "ms": round(ems, 4), "steps": n_e, "stage_ms": est,
+            "gather": {"bytes": gbytes, "achieved": round(gbytes / (gms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                       "frac": round(gbytes / (gms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+            "gemm_tflops": round(6.0 * Rr * H * F / ((est["gate_up"] + est["down"]) * 1e-3) / 1e12, 1),
+            "sample": "the most loaded rank of the group; every source sends the chunk sizes of this batch's routing; "
+                      "payload N(0,1); the two All-to-All-Vs themselves are not run"}
     if args.dispatch_backward and not fp8:
         # dy plays the gradient of the layer output; the forward's y_perm, maps and gates are reused
         res = {}

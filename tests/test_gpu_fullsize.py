@@ -337,3 +337,39 @@ def test_full_size_permute_variants(name, by_score, pad):
     assert torch.equal(x_perm[owned].view(torch.int16), src[owned].view(torch.int16))
     rest = x_perm[~owned].float()
     assert rest.numel() == 0 or bool((rest == (0.0 if pad else 5.0)).all())
+
+
+@pytest.mark.parametrize("S,El,H,mean_rows", [(8, 8, 6144, 1024), (8, 1, 6144, 2048), (64, 4, 4096, 96)])
+def test_full_size_chunk_gather(S, El, H, mean_rows):
+    """The gather of an expert-parallel share at bench size (8 sources x 8 local experts of the G8T8 shape; one local
+    expert; many sources).  The oracle runs the same gather on a 16-byte payload that carries each row's number, which
+    gives the source row of every destination row; every destination row must be that source row, whole."""
+    import torch
+    import paper_2504_14960_amd as moe
+    rng = np.random.default_rng(S * 1000 + El)
+    rows = rng.poisson(mean_rows, size=S * El).astype(np.int32)
+    rows[rng.random(S * El) < 0.1] = 0
+    R = int(rows.sum())
+    order = np.array([s * El + e for e in range(El) for s in range(S)], dtype=np.int32)
+    ids = np.zeros((R, 4), dtype=np.int32)
+    ids[:, 0] = np.arange(R)
+    want_ids, want_rows, want_goff, total = oracle.sort_chunks(ids, rows, order, group=S)
+    assert total == R
+    src = torch.randn((R, H), dtype=torch.bfloat16, device="cuda")
+    dst = torch.zeros((R + 5, H), dtype=torch.bfloat16, device="cuda")
+    rows_out = torch.empty(S * El, dtype=torch.int32, device="cuda")
+    goff = torch.empty(El + 1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(moe.sort_chunks_workspace_bytes(S * El), dtype=torch.uint8, device="cuda")
+    moe.sort_chunks(src, to_dev(rows), to_dev(order), S, dst, rows_out, goff, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host(rows_out), want_rows)
+    np.testing.assert_array_equal(to_host(goff), want_goff)
+    from_row = torch.from_numpy(want_ids[:, 0].astype(np.int64)).cuda()
+    assert torch.equal(dst[:R].view(torch.int16), src.view(torch.int16)[from_row])
+    assert not dst[R:].any(), "rows past the total must be left untouched"
+    # and the way back restores the received layout
+    inv = np.array([e * S + s for s in range(S) for e in range(El)], dtype=np.int32)
+    back = torch.zeros_like(src)
+    moe.sort_chunks(dst, rows_out, to_dev(inv), 0, back, None, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(back.view(torch.int16), src.view(torch.int16))
