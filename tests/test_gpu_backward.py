@@ -318,3 +318,15 @@ def test_layer_training_step_in_two_calls(base, kw):
     _assert_grad_close(dwr.cpu().numpy(), want["dw_router"], "dw_router")
     if inp.bias is not None:
         _assert_grad_close(dbias.cpu().numpy(), want["dbias"], "dbias")
+    # every sum over tokens has a fixed order: a second backward on a dirtied workspace gives the same bits
+    grads = (dx, dwr, dbias, dwg, dwu, dwd)
+    first = [g.clone() for g in grads]
+    bws.fill_(0x5a)
+    for g in grads:
+        g.fill_(float("nan"))
+    moe.layer_backward(d["x"], d["w_router"], d["w_gate"], d["w_up"], wgu_t, wd_t, to_dev(dy), K, cfg.renormalize,
+                       capacity, fws, gu, dx, dwr, dbias, dwg, dwu, dwd, bws)
+    torch.cuda.synchronize()
+    for name, a, b in zip(("dx", "dw_router", "dbias", "dw_gate", "dw_up", "dw_down"), first, grads):
+        bits = torch.int16 if a.dtype == torch.bfloat16 else torch.int32
+        assert torch.equal(a.view(bits), b.view(bits)), f"{name} differs between two runs"
