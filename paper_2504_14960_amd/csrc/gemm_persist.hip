@@ -445,7 +445,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
             bfg[buf][q - FM] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sb + b_off[q - FM] + c));
     };
     auto mfma_one = [&](int buf, int m) {
-        const int i = m / FN, j = m % FN;
+        // boustrophedon over the wave's blocks: successive MFMAs share one operand fragment
+        const int i = m / FN, j = (i & 1) ? FN - 1 - m % FN : m % FN;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfg[buf][j], af[buf][i], acc[i][j], 0, 0, 0);
     };
     // one k-step in issue order: NSLOT slots of {MPS MFMAs on set mf_buf; up to

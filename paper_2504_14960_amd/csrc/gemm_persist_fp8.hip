@@ -278,7 +278,8 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
         return v;
     };
     auto mfma_one = [&](int buf, int m) {
-        const int i = m / FN, j = m % FN;
+        // boustrophedon over the wave's blocks: successive MFMAs share one operand fragment
+        const int i = m / FN, j = (i & 1) ? FN - 1 - m % FN : m % FN;
         // E4M3 x E4M3 (formats 0, 0), no block scales; weight fragment first as in the bf16 kernels
         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(frag(bfh[buf][j]), frag(afh[buf][i]), acc[i][j],
                                                                     0, 0, 0, 0, 0, 0);
