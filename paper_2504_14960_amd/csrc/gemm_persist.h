@@ -38,7 +38,7 @@ struct PTile {
 
 // Every wave keeps the whole schedule in registers: lane l describes experts
 // 4l .. 4l+3 (first row, row count, exclusive prefix of M-tile counts).
-template <int BM>
+template <int BM, bool BY_ROUND = true>
 struct TileSched {
     int lo[4], n[4], pex[4], pend;
     int MT, ntn, per, nwx, wgx, xcd, total;
@@ -83,9 +83,29 @@ struct TileSched {
         constexpr int MG = 8;
         PTile t;
         t.a = A; t.b0 = B0; t.b1 = B1; t.a_lim = 0; t.b_lim = 0; t.row0 = 0; t.rows = 0; t.n0 = 0; t.kt = 0; t.krows = 0;
-        const int j = wgx + i * nwx;
-        const int L = xcd * per + j;
-        t.valid = (j < per) && (L < total);
+        // BY_ROUND: whole rounds (one tile per workgroup of the launch) are dealt to the XCDs round by round: in
+        // round i XCD x runs the nwx consecutive tiles from (8 i + x) nwx on, so at any time the eight XCDs work on
+        // neighbouring stretches of the list and what they have in common (activation panels of one M-group) is
+        // fetched from memory once and found in the memory-side cache by the others.  The tiles left over after
+        // the last whole round are cut into eight contiguous shares.  Otherwise every XCD takes a contiguous
+        // eighth of the list.
+        int L;
+        if (BY_ROUND && (gridDim.x & 7) == 0) {
+            const int round_tiles = 8 * nwx, whole = total / round_tiles;
+            if (i < whole) {
+                L = (i * 8 + xcd) * nwx + wgx;
+                t.valid = true;
+            } else {
+                const int left = total - whole * round_tiles, share = (left + 7) >> 3;
+                const int j = wgx + (i - whole) * nwx;
+                L = whole * round_tiles + xcd * share + j;
+                t.valid = (j < share) && (L < total);
+            }
+        } else {
+            const int j = wgx + i * nwx;
+            L = xcd * per + j;
+            t.valid = (j < per) && (L < total);
+        }
         if (!t.valid) return t;
         const int qm = L / ntn;
         int hit = -1, my_p = 0, my_end = 0, my_lo = 0, my_n = 0;

@@ -263,7 +263,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const uint8_t* const B1b = SWIGLU ? reinterpret_cast<const uint8_t*>(B1) : B0b;
 
     typename std::conditional<KMAJ, WgradSchedKM<BM, BN>,
-                              typename std::conditional<GROUPK, WgradSched<BM, BN>, TileSched<BM>>::type>::type sched;
+                              typename std::conditional<GROUPK, WgradSched<BM, BN>, TileSched<BM, !IDLE_SKIP>>::type>::type sched;
     if constexpr (GROUPK)
         sched.init(offsets, E, ntn, N, lane);
     else
