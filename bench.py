@@ -31,7 +31,7 @@ NSETS = 4                   # rotating activation/workspace sets (defeats the 25
 # HBM traffic of one gate/up GEMM launch at the default workload, from the
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (bytes);
 # None for workloads that were not profiled.
-MEASURED_TRAFFIC = {"mixtral8x22b": 10.93e9}   # 10.39 GB fetched (L2 misses: HBM + Infinity Cache) + 0.54 GB written
+MEASURED_TRAFFIC = {"mixtral8x22b": 11.75e9}   # 11.21 GB fetched (L2 misses: HBM + Infinity Cache) + 0.54 GB written
 
 
 def parse_args():
