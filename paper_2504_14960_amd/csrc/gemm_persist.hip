@@ -262,6 +262,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const uint8_t* const B0b = reinterpret_cast<const uint8_t*>(B0);
     const uint8_t* const B1b = SWIGLU ? reinterpret_cast<const uint8_t*>(B1) : B0b;
 
+    // tiles are dealt to the XCDs round by round, except in the many-expert instantiations (measured: there the
+    // gate/up GEMM loses 1 %, and the two GEMMs of a layer must walk the rows in the same order)
     typename std::conditional<KMAJ, WgradSchedKM<BM, BN>,
                               typename std::conditional<GROUPK, WgradSched<BM, BN>, TileSched<BM, !IDLE_SKIP>>::type>::type sched;
     if constexpr (GROUPK)
