@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import assert_close, ep_chunk_orders, to_dev, to_host, values
+from helpers import assert_close, ep_chunk_orders, guard_margins, to_dev, to_host, values
 from moe_inputs import get_config, make_layer_inputs, make_tokens
 
 pytestmark = pytest.mark.gpu
@@ -183,6 +183,7 @@ def _ep_group_on_gpu(xs, inp, cfg, capacity):
 def test_ep_group_rank_by_rank_equals_the_one_gpu_layer(name, scale, S, capacity):
     cfg = get_config(name).scaled(**scale)
     inp = make_layer_inputs(cfg)
+    guard_margins(inp, cfg.K)     # no token whose top-k choice hangs on fp32 summation order
     cuts = np.linspace(0, cfg.T, S + 1).astype(int)
     cuts[1] = max(1, cuts[1] // 3)                         # ragged: one rank holds few tokens
     xs = [inp["x"][cuts[s]:cuts[s + 1]] for s in range(S)]
