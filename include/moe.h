@@ -1,7 +1,9 @@
 /*
- * moe.h -- C ABI of the MI355X (gfx950) MoE-layer forward hot path.
+ * moe.h -- C ABI of the MI355X (gfx950) MoE-layer hot path: the forward of the
+ * layer's four stages, their backward, the FP8 expert FFN and one GPU's step of
+ * expert-parallel dispatch.
  *
- * The library computes, on one GPU with all experts local, the forward of the
+ * The library computes, on one GPU with all experts local, the
  * Mixture-of-Experts layer of arXiv 2504.14960:
  *
  *     y = sum_e g_e(x) * f_e(x)                       (Eq. 1, Section 3.1.1)
@@ -336,6 +338,9 @@ moe_status_t moe_grouped_gemm_swiglu_backward(const void* x_perm, const void* h,
  * expert (0 = none).  Host only. */
 size_t moe_layer_workspace_bytes(int T, int H, int E, int K, int F, int Fs, int capacity,
                                  moe_dtype_t dt);
+/* The same for a layer without a shared expert (Fs = 0): the forward workflow of
+ * Section 3.3 as the paper states it. */
+size_t moe_workspace_bytes(int T, int H, int E, int K, int F, int capacity, moe_dtype_t dt);
 
 /*
  * The training step of the layer in two calls (bf16, no shared expert; Section
@@ -482,6 +487,19 @@ moe_status_t moe_probe_mfma_bf16(const void* image, int iters, int workgroups, f
  * FLOP. */
 moe_status_t moe_probe_mfma_fp8(const void* image, int iters, int workgroups, float* sink,
                                 uint64_t* ticks, moe_stream_t stream);
+
+/*
+ * Clock sample of the grouped bf16 GEMMs (measurement aid, like the probes
+ * above).  ticks: DEVICE memory, 2 x uint64, or NULL to switch the sampling off
+ * (the default).  While set, workgroup 0 of every grouped bf16 GEMM launch that
+ * runs on the persistent kernel (forward, backward) writes ticks[0] = shader
+ * clocks and ticks[1] = 100 MHz reference clocks it spent in the kernel, so
+ * ticks[0] / ticks[1] * 100 is the shader clock in MHz the launch ran at.  The
+ * pointer is process-wide host state read at launch time (not thread-safe); the
+ * cells keep the last launch's values and stay untouched by a launch whose
+ * workgroup 0 has no tile.  Always MOE_OK unless ticks is misaligned.
+ */
+moe_status_t moe_gemm_clock_sample(uint64_t* ticks);
 
 /* Tuning knobs for experiments (process-wide, not thread-safe; defaults are
  * the tuned ones).  Unknown names return MOE_ERR_INVALID_ARG.  Names:

@@ -100,6 +100,10 @@ def lib() -> C.CDLL:
     L.moe_expert_gate_up_saving.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, vp, vp]
     L.moe_layer_workspace_bytes.restype = sz
     L.moe_layer_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
+    L.moe_workspace_bytes.restype = sz
+    L.moe_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    L.moe_gemm_clock_sample.restype = i
+    L.moe_gemm_clock_sample.argtypes = [vp]
     L.moe_layer_workspace_layout.restype = i
     L.moe_layer_workspace_layout.argtypes = [i, i, i, i, i, i, i, i, C.POINTER(sz), i]
     L.moe_layer_forward.restype = i
@@ -427,6 +431,17 @@ def probe_mfma_fp8(image: torch.Tensor, iters: int, workgroups: int, sink: torch
 
 def layer_workspace_bytes(T: int, H: int, E: int, K: int, F: int, Fs: int, capacity: int, dtype: int) -> int:
     return int(lib().moe_layer_workspace_bytes(T, H, E, K, F, Fs, capacity, dtype))
+
+
+def workspace_bytes(T: int, H: int, E: int, K: int, F: int, capacity: int, dtype: int) -> int:
+    return int(lib().moe_workspace_bytes(T, H, E, K, F, capacity, dtype))
+
+
+def gemm_clock_sample(ticks: Optional[torch.Tensor]) -> None:
+    """ticks: int64 device tensor of 2 elements that the following grouped bf16 GEMM launches fill, or None."""
+    if ticks is not None and (ticks.dtype != torch.int64 or ticks.numel() < 2):
+        raise ValueError("ticks must be an int64 tensor with at least 2 elements")
+    _check(lib().moe_gemm_clock_sample(_ptr(ticks)))
 
 
 _LAYOUT_NAMES = ("logits", "topk_idx", "topk_gate", "expert_counts", "expert_offsets", "row_of_assign",

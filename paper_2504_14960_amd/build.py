@@ -24,10 +24,23 @@ FLAGS = [
 
 
 def _deps(src: str):
+    """Every header of csrc/ counts for every object: the sources include them in changing combinations,
+    and a stale object is worse than a few seconds of rebuilding."""
     yield os.path.join(CSRC, src)
-    yield os.path.join(CSRC, "common.h")
-    yield os.path.join(CSRC, "gemm_tile.h")
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith(".h"):
+            yield os.path.join(CSRC, name)
     yield os.path.join(HERE, "..", "include", "moe.h")
+
+
+def stale_sources():
+    """Sources and headers newer than the built library (empty when the library is up to date)."""
+    if not os.path.exists(LIB):
+        return ["libmoe_hip.so is missing"]
+    t = os.path.getmtime(LIB)
+    files = [os.path.join(CSRC, n) for n in sorted(os.listdir(CSRC)) if n.endswith((".h", ".hip"))]
+    files.append(os.path.join(HERE, "..", "include", "moe.h"))
+    return [os.path.relpath(f, HERE) for f in files if os.path.getmtime(f) > t]
 
 
 def _compile(src: str, force: bool) -> str:

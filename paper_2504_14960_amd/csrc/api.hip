@@ -568,6 +568,10 @@ size_t moe_layer_workspace_bytes(int T, int H, int E, int K, int F, int Fs, int 
     return layer_layout(T, H, E, K, F, Fs, capacity, dt).total;
 }
 
+size_t moe_workspace_bytes(int T, int H, int E, int K, int F, int capacity, moe_dtype_t dt) {
+    return moe_layer_workspace_bytes(T, H, E, K, F, 0, capacity, dt);
+}
+
 moe_status_t moe_layer_workspace_layout(int T, int H, int E, int K, int F, int Fs, int capacity,
                                         moe_dtype_t dt, size_t* byte_offsets, int n) {
     if (byte_offsets == nullptr || n < 11) return fail(MOE_ERR_INVALID_ARG, "moe_layer_workspace_layout: need room for 11 offsets");
@@ -865,6 +869,13 @@ moe_status_t moe_probe_mfma_fp8(const void* image, int iters, int workgroups, fl
     launch_probe_mfma_fp8(image, iters, workgroups, sink, reinterpret_cast<unsigned long long*>(ticks),
                           static_cast<hipStream_t>(stream));
     return check_launch(fn);
+}
+
+moe_status_t moe_gemm_clock_sample(uint64_t* ticks) {
+    if (reinterpret_cast<uintptr_t>(ticks) & 7u)
+        return fail(MOE_ERR_INVALID_ARG, "moe_gemm_clock_sample: ticks is not 8-byte aligned");
+    moe::set_persist_clock_sample(reinterpret_cast<unsigned long long*>(ticks));
+    return MOE_OK;
 }
 
 moe_status_t moe_set_option(const char* name, int value) {

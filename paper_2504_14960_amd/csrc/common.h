@@ -69,6 +69,8 @@ void launch_combine_backward(const void* dy, const void* y_perm, const int32_t* 
 // persistent grouped-GEMM kernels: workgroups per launch, 0 = one per compute unit
 void set_persist_workgroups(int n);
 void set_persist_idle_skip(int v);   // -1 auto, 0 off, 1 on
+// device cells {shader-clock ticks, 100 MHz ticks} that workgroup 0 of every later persistent bf16 GEMM launch fills
+void set_persist_clock_sample(unsigned long long* ticks);
 
 // grouped NT GEMMs of the expert FFN.  phase bit 0: gate/up + SwiGLU (x_perm ->
 // h); bit 1: down projection (h -> y_perm).  Returns false if unsupported.

@@ -25,14 +25,9 @@
 
 namespace moe {
 
-#ifdef MOE_PIPE_TIMING
-// instrumentation build only: per-workgroup, per-wave tick counters
-// {loops, epilogues, whole kernel, tiles, 100 MHz clock over the kernel}
-__device__ unsigned long long g_persist_ticks[1024 * 8 * 8];
-#endif
-
 static int g_persist_workgroups = 0;  // 0: one per compute unit
 static int g_persist_idle_skip = -1;  // -1: chosen from the expert count; 0 / 1: forced
+static unsigned long long* g_persist_ticks = nullptr;  // device cell pair of the clock sample, or none
 
 int persist_grid() {
     // every one of the 8 tile shares needs a workgroup with its residue mod 8
@@ -213,7 +208,7 @@ template <int BM, int BN, int WGM, int WGN, int MODE, bool GROUPK = false, bool 
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, bf16_t* __restrict__ GU,
-    int ntn, int ldb) {
+    int ntn, int ldb, unsigned long long* __restrict__ ticks) {
     static_assert(!GROUPK || MODE == 0, "the weight-gradient form has a plain epilogue");
     static_assert(!KMAJ || (GROUPK && BM == 256 && BN == 256 && WGM * WGN == 8), "row-major form: 256 x 256 tiles, 8 waves");
     constexpr bool SWIGLU = MODE == 1 || MODE == 2;
@@ -248,11 +243,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     static_assert(NW * 32 * FO * 64 <= A_BYTES, "epilogue patches must fit into one activation slot");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-#ifdef MOE_PIPE_TIMING
-    const unsigned long long tk_entry = __builtin_amdgcn_s_memtime();
-    const unsigned long long rt_entry = __builtin_amdgcn_s_memrealtime();
-    unsigned long long tk_loop = 0, tk_epi = 0, tk_tiles = 0;
-#endif
+    // clock sample (ticks != NULL): shader-clock and 100 MHz reference ticks workgroup 0 spends in the kernel
+    const bool sample = ticks != nullptr && blockIdx.x == 0;
+    unsigned long long tk_entry = 0, rt_entry = 0;
+    if (sample) {
+        tk_entry = __builtin_amdgcn_s_memtime();
+        rt_entry = __builtin_amdgcn_s_memrealtime();
+    }
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -505,9 +502,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     int l0 = 0, l1 = A_BYTES, l2 = 2 * A_BYTES;  // activation slots of k-tiles kt, kt+1, kt+2
     int e0 = 0, e1 = B_BYTES;                    // weight slots of k-tiles kt, kt+1
     for (;;) {
-#ifdef MOE_PIPE_TIMING
-        const unsigned long long tk_l0 = __builtin_amdgcn_s_memtime();
-#endif
         // (IDLE_SKIP instantiations, chosen for launches with many experts, i.e. many ragged tails; the test costs
         // the plain kernel half a per cent.)  A wave whose rows of the tile all lie past the tile's last valid row
         // (ragged tail of an expert) has nothing to multiply: it keeps issuing its share of the loads and meeting the barriers, and leaves the
@@ -566,9 +560,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
                 for (int q = 0; q < NREAD; ++q) read_one(a_region + l0, b_region + e0, 0, 0, q);
             }
         }
-#ifdef MOE_PIPE_TIMING
-        const unsigned long long tk_l1 = __builtin_amdgcn_s_memtime();
-#endif
         // Epilogue.  The activation slot that held the last k-tile (now l2) is
         // idle: every wave finished reading it before the last barrier, and the
         // next loads into it are issued only after the barrier below.
@@ -589,23 +580,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave is done with its patch
         __builtin_amdgcn_s_barrier();
-#ifdef MOE_PIPE_TIMING
-        tk_loop += tk_l1 - tk_l0;
-        tk_epi += __builtin_amdgcn_s_memtime() - tk_l1;
-        ++tk_tiles;
-#endif
     }
     wait_vmcnt0();  // loads past the end of the last tile may still be landing in LDS
-#ifdef MOE_PIPE_TIMING
-    if (lane == 0 && blockIdx.x < 1024) {
-        unsigned long long* o = g_persist_ticks + ((size_t)blockIdx.x * 8 + wave) * 8;
-        o[0] = tk_loop;
-        o[1] = tk_epi;
-        o[2] = __builtin_amdgcn_s_memtime() - tk_entry;
-        o[3] = tk_tiles;
-        o[4] = __builtin_amdgcn_s_memrealtime() - rt_entry;
+    if (sample && tid == 0) {
+        ticks[0] = __builtin_amdgcn_s_memtime() - tk_entry;
+        ticks[1] = __builtin_amdgcn_s_memrealtime() - rt_entry;
     }
-#endif
 }
 
 template <int BM, int BN, int WGM, int WGN, int MODE>
@@ -628,7 +608,7 @@ void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int
     const int grid = min(persist_grid(), grid_for(r_max, E, BM, ntn));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A), offsets, E, N,
                        K, static_cast<const bf16_t*>(B0), static_cast<const bf16_t*>(B1), static_cast<bf16_t*>(C),
-                       static_cast<bf16_t*>(GU), ntn, 0);
+                       static_cast<bf16_t*>(GU), ntn, 0, g_persist_ticks);
 }
 
 // dw[e] = 0 for every expert without rows (the persistent weight-gradient kernel gives them no tiles)
@@ -658,7 +638,7 @@ void launch_persist_groupk(const void* A, const void* B, const int32_t* offsets,
     const int grid = (int)min((long long)persist_grid(), (tiles + 7) / 8 * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A), offsets, E, N,
                        ld, static_cast<const bf16_t*>(B), static_cast<const bf16_t*>(B), static_cast<bf16_t*>(C),
-                       static_cast<bf16_t*>(nullptr), M, 0);
+                       static_cast<bf16_t*>(nullptr), M, 0, g_persist_ticks);
 }
 
 // weight gradients straight from the row-major activations (no transposed copies): see the kernel's KMAJ form
@@ -679,7 +659,7 @@ void launch_persist_groupk_rowmajor(const void* A, int lda, const void* B, int l
     const int grid = (int)min((long long)persist_grid(), (tiles + 7) / 8 * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WGM * WGN * 64), smem, s, static_cast<const bf16_t*>(A), offsets, E, N,
                        lda, static_cast<const bf16_t*>(B), static_cast<const bf16_t*>(B), static_cast<bf16_t*>(C),
-                       static_cast<bf16_t*>(const_cast<void*>(zero_row)), M, ldb);
+                       static_cast<bf16_t*>(const_cast<void*>(zero_row)), M, ldb, g_persist_ticks);
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -694,6 +674,7 @@ void run_persist_pair(const void* x_perm, const int32_t* offsets, int r_max, int
 
 void set_persist_workgroups(int n) { g_persist_workgroups = n; }
 void set_persist_idle_skip(int v) { g_persist_idle_skip = v; }
+void set_persist_clock_sample(unsigned long long* ticks) { g_persist_ticks = ticks; }
 bool persist_idle_skip(int E) { return g_persist_idle_skip < 0 ? E >= 16 : g_persist_idle_skip != 0; }
 
 // C [rows, N] = A [rows, K] . B[e]^T with B [E, N, K], rows grouped by expert (bf16): the

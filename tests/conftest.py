@@ -12,6 +12,18 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_report_header(config):
+    """Which HIP library this run loads: its hash, and a warning if a source is newer than it."""
+    import hashlib
+    from paper_2504_14960_amd.build import LIB, stale_sources
+    if not os.path.exists(LIB):
+        return "libmoe_hip.so: MISSING (python -m paper_2504_14960_amd.build)"
+    digest = hashlib.sha256(open(LIB, "rb").read()).hexdigest()[:16]
+    stale = stale_sources()
+    note = f"  STALE: newer sources {stale}" if stale else "  (up to date with csrc/)"
+    return f"libmoe_hip.so sha256 {digest}{note}"
+
+
 def _have_gpu() -> bool:
     try:
         import torch

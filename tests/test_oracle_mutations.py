@@ -108,7 +108,11 @@ def _run_mutant(m, tmp):
     env = dict(os.environ, MOE_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider",
                         *[os.path.join(ROOT, "tests", p) for p in pins]], cwd=ROOT, env=env, capture_output=True, text=True)
-    return name, ("caught" if r.returncode == 1 else "survived" if r.returncode == 0 else "error"), r.stdout[-300:]
+    # a mutant that writes past a buffer may also take the child down (signal, or a non-1 status after a test
+    # already failed): that run has failed a pin just the same
+    crashed = r.returncode < 0 or r.returncode in (134, 139)
+    caught = r.returncode == 1 or crashed or (r.returncode != 0 and " failed" in r.stdout)
+    return name, ("caught" if caught else "survived" if r.returncode == 0 else "error"), r.stdout[-300:]
 
 
 def test_every_planted_mistake_is_caught_by_a_pin():
