@@ -2,11 +2,15 @@
 launch configuration bench.py times.
 
 Routing, maps, counts and offsets are compared in full (bit-exact).  The expert
-FFN and the combine are compared on sampled tokens: for every sampled token the
-oracle evaluates each of its kept (token, expert) rows one by one and then the
-gate-weighted sum, so every sampled output value is an independent full-size
-result.  Properties that hold at any size (row copies, exact zeros for fully
-dropped tokens) are checked on everything.
+FFN and the combine are compared on samples the oracle evaluates one row at a
+time, so every sampled output value is an independent full-size result:
+  * h and y_perm on the first and the last valid row of EVERY 256-row M-tile of
+    every expert, whole rows (all N-tiles), each row judged on its own: a single
+    wrong output tile (m, n) of either GEMM fails, whichever workgroup, round or
+    remainder share of the persistent schedule it fell into;
+  * h, y_perm and y on the rows of 512 random tokens (all their assignments).
+Properties that hold at any size (row copies, exact zeros for fully dropped
+tokens) are checked on everything.
 """
 import numpy as np
 import pytest
@@ -17,7 +21,19 @@ from helpers import (LOGIT_ATOL, assert_close, capacity_rows, guard_margins, to_
 
 pytestmark = pytest.mark.gpu
 
-N_SAMPLE_TOKENS = 24
+N_SAMPLE_TOKENS = 512      # tokens whose layer output is compared (all their kept rows go through the oracle)
+N_SAMPLE_TOKENS_FP8 = 48   # the FP8 oracle quantises on one core
+M_TILE = 256               # rows per output tile of the grouped GEMM kernels
+
+
+def tile_edge_rows(offsets, counts):
+    """First and last valid row of every M_TILE-row block of every expert's row range."""
+    rows = []
+    for e, n in enumerate(counts):
+        lo = int(offsets[e])
+        for m0 in range(0, int(n), M_TILE):
+            rows += [lo + m0, lo + min(m0 + M_TILE, int(n)) - 1]
+    return np.unique(np.array(rows, dtype=np.int64))
 
 
 def _run_stages(inp, capacity):
@@ -102,7 +118,9 @@ def test_full_size_layer(name):
     pool = np.nonzero(kept_any)[0]
     tokens = np.sort(rng.choice(pool, size=min(N_SAMPLE_TOKENS, pool.size), replace=False))
     rows = np.unique(perm.row_of_assign.reshape(T, K)[tokens].reshape(-1))
-    rows = rows[rows >= 0]
+    edge_rows = tile_edge_rows(perm.offsets, perm.counts)
+    assert edge_rows.size >= int(np.ceil(perm.counts / M_TILE).sum())      # at least one row per tile
+    rows = np.union1d(rows[rows >= 0], edge_rows)
     y_perm_ref = np.zeros((rows.size, H))
     h_ref = np.zeros((rows.size, F))
     expert_of_row = np.searchsorted(perm.offsets, rows, side="right") - 1
@@ -113,8 +131,15 @@ def test_full_size_layer(name):
         y_perm_ref[sel], h_ref[sel] = ye, he
     import torch
     dev_rows = torch.from_numpy(rows.astype(np.int64)).cuda()
-    assert_close(to_host(o["h"][dev_rows]), h_ref, bf16, f"h rows ({name})")
-    assert_close(to_host(o["y_perm"][dev_rows]), y_perm_ref, bf16, f"y_perm rows ({name})")
+    got_h, got_yp = to_host(o["h"][dev_rows]), to_host(o["y_perm"][dev_rows])
+    assert_close(got_h, h_ref, bf16, f"h rows ({name})")
+    assert_close(got_yp, y_perm_ref, bf16, f"y_perm rows ({name})")
+    # every tile-edge row on its own, so one wrong tile cannot hide in the norm of the whole sample
+    for i in np.nonzero(np.isin(rows, edge_rows))[0]:
+        assert_close(got_h[i], h_ref[i], bf16, f"h row {rows[i]} ({name})")
+        assert_close(got_yp[i], y_perm_ref[i], bf16, f"y_perm row {rows[i]} ({name})")
+    print(f"[{name}] compared {rows.size} rows of h / y_perm ({edge_rows.size} tile-edge rows) and {tokens.size} "
+          "tokens of y", flush=True)
 
     # compact maps for the sampled tokens, then the oracle's combine
     remap = {int(r): i for i, r in enumerate(rows)}
@@ -167,9 +192,10 @@ def test_full_size_fp8_expert_ffn(name):
     rng = np.random.default_rng(cfg.seed + 1)
     kept_any = (perm.row_of_assign.reshape(T, K) >= 0).any(axis=1)
     pool = np.nonzero(kept_any)[0]
-    tokens = np.sort(rng.choice(pool, size=min(N_SAMPLE_TOKENS, pool.size), replace=False))
+    tokens = np.sort(rng.choice(pool, size=min(N_SAMPLE_TOKENS_FP8, pool.size), replace=False))
     rows = np.unique(perm.row_of_assign.reshape(T, K)[tokens].reshape(-1))
-    rows = rows[rows >= 0]                                  # ascending = grouped by expert
+    # plus the first and last row of every 256-row block of every expert (the FP8 kernels' tiles are 256 rows too)
+    rows = np.union1d(rows[rows >= 0], tile_edge_rows(perm.offsets, perm.counts))   # ascending = grouped by expert
     expert_of_row = np.searchsorted(perm.offsets, rows, side="right") - 1
     sub_offsets = np.concatenate([[0], np.cumsum(np.bincount(expert_of_row, minlength=E))]).astype(np.int32)
     xq_rows = oracle.fp8_quantize(np.ascontiguousarray(t["x"][token_of_row[rows]]), sc["x"])[0]
