@@ -127,6 +127,27 @@ moe_status_t moe_permute(const void* x, const int32_t* topk_idx, int T, int H, i
                          moe_stream_t stream);
 
 /*
+ * moe_permute for callers that cannot hand over (or allocate) a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid device
+ * allocation.  Same arguments, outputs, limits and errors as moe_permute, minus
+ * the workspace: the chunk histograms live in a 1 MiB array inside the library's
+ * device image (one copy per GPU, held until the process ends).  Nothing is
+ * allocated or freed, here or in anything this calls.  The call is refused with
+ * MOE_ERR_UNSUPPORTED when moe_permute_workspace_bytes(T, K, E) exceeds 1 MiB
+ * (ceil(T*K/1024) * E > 262144; every benchmark shape is far below).  The array
+ * keeps the previous call's contents; nothing in it has to start at zero (every
+ * cell that is read was written earlier in the same call).  All calls on one GPU
+ * share the array: calls that overlap in time on one GPU (different streams)
+ * race; calls on one stream, or ordered by events, are fine.  The first call on
+ * a device looks the array's address up (not to be captured into a graph: make
+ * one plain call first).
+ */
+moe_status_t moe_permute_noalloc(const void* x, const int32_t* topk_idx, int T, int H, int E, int K,
+                                 int capacity, moe_dtype_t dt, void* x_perm, int32_t* expert_counts,
+                                 int32_t* expert_offsets, int32_t* row_of_assign,
+                                 int32_t* assign_of_row, moe_stream_t stream);
+
+/*
  * Two variants of a2 that capacity-based MoE training uses next to the paper's
  * default (Eq. 4 fixes the capacity; Section 3.3 drops by position):
  *

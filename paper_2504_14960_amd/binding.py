@@ -56,6 +56,8 @@ def lib() -> C.CDLL:
     L.moe_router_topk.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp]
     L.moe_permute.restype = i
     L.moe_permute.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.moe_permute_noalloc.restype = i
+    L.moe_permute_noalloc.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp]
     L.moe_grouped_gemm_swiglu.restype = i
     L.moe_grouped_gemm_swiglu.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, i, vp, vp, vp]
     L.moe_expert_gate_up.restype = i
@@ -197,6 +199,20 @@ def permute(x: Optional[torch.Tensor], topk_idx: torch.Tensor, E: int, capacity:
                              _ptr(expert_counts), _ptr(expert_offsets), _ptr(row_of_assign),
                              _ptr(assign_of_row), _ptr(workspace), workspace.numel() * workspace.element_size(),
                              _stream()))
+
+
+def permute_noalloc(x: Optional[torch.Tensor], topk_idx: torch.Tensor, E: int, capacity: int,
+                    x_perm: Optional[torch.Tensor], expert_counts: torch.Tensor, expert_offsets: torch.Tensor,
+                    row_of_assign: torch.Tensor, assign_of_row: torch.Tensor, H: Optional[int] = None,
+                    dtype: int = MOE_BF16) -> None:
+    T, K = topk_idx.shape
+    if x is not None:
+        H, dtype = x.shape[1], _dt(x)
+    elif H is None:
+        H = 8
+    _check(lib().moe_permute_noalloc(_ptr(x), _ptr(topk_idx), T, H, E, K, int(capacity), dtype, _ptr(x_perm),
+                                     _ptr(expert_counts), _ptr(expert_offsets), _ptr(row_of_assign),
+                                     _ptr(assign_of_row), _stream()))
 
 
 def grouped_gemm_swiglu(x_perm: torch.Tensor, expert_offsets: torch.Tensor, w_gate: torch.Tensor,

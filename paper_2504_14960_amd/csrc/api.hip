@@ -167,6 +167,29 @@ moe_status_t moe_permute(const void* x, const int32_t* topk_idx, int T, int H, i
     return check_launch(fn);
 }
 
+moe_status_t moe_permute_noalloc(const void* x, const int32_t* topk_idx, int T, int H, int E, int K,
+                                 int capacity, moe_dtype_t dt, void* x_perm, int32_t* expert_counts,
+                                 int32_t* expert_offsets, int32_t* row_of_assign,
+                                 int32_t* assign_of_row, moe_stream_t stream) {
+    static const char* fn = "moe_permute_noalloc";
+    if (moe_status_t st = check_dims(fn, T, H, E, K, dt)) return st;
+    // the size limit first: it needs no GPU
+    const size_t need = permute_workspace_bytes(T, K, E);
+    if (need > permute_scratch_bytes())
+        return fail(MOE_ERR_UNSUPPORTED,
+                    "%s: T*K=%lld assignments over E=%d experts need %zu bytes of scratch, the library holds %zu; "
+                    "use moe_permute with a workspace",
+                    fn, (long long)T * K, E, need, permute_scratch_bytes());
+    if (T == 0)   // no scratch involved
+        return moe_permute(x, topk_idx, T, H, E, K, capacity, dt, x_perm, expert_counts, expert_offsets,
+                           row_of_assign, assign_of_row, nullptr, 0, stream);
+    hipError_t err = hipSuccess;
+    int32_t* ws = permute_scratch(&err);
+    if (ws == nullptr) return fail(MOE_ERR_LAUNCH, "%s: no address for the scratch array: %s", fn, hipGetErrorString(err));
+    return moe_permute(x, topk_idx, T, H, E, K, capacity, dt, x_perm, expert_counts, expert_offsets, row_of_assign,
+                       assign_of_row, ws, permute_scratch_bytes(), stream);
+}
+
 size_t moe_permute_variant_workspace_bytes(int T, int K, int E) {
     if (T < 0 || K <= 0 || E <= 0) return 0;
     return permute_variant_workspace_bytes(T, K, E);

@@ -58,6 +58,10 @@ void launch_permute(const void* x, const int32_t* idx, int T, int H, int E, int 
                     int r_max, moe_dtype_t dt, void* x_perm, int32_t* counts, int32_t* offsets,
                     int32_t* row_of_assign, int32_t* assign_of_row, void* ws, hipStream_t s);
 
+// the library's own scratch for moe_permute_noalloc: its size, and its address on the current device
+size_t permute_scratch_bytes();
+int32_t* permute_scratch(hipError_t* err);
+
 void launch_combine(const void* y_perm, const int32_t* row_of_assign, const float* gate,
                     const void* addend, int T, int H, int K, int r_max, moe_dtype_t dt, void* y,
                     hipStream_t s);

@@ -12,6 +12,8 @@
 //                           with wave ballots and writes both maps.
 //   3. permute_copy_kernel  one wave per token: the row is read once with
 //                           16-byte lanes and stored to each kept destination.
+#include <mutex>
+
 #include "fp8_convert.h"
 
 namespace moe {
@@ -20,6 +22,15 @@ namespace {
 
 constexpr int kChunk = 1024;  // assignments per workgroup
 constexpr int kUnits = kChunk / 64;
+
+// Scratch of moe_permute_noalloc: the chunk histograms of one call (the role `workspace` plays in
+// moe_permute).  One copy per GPU, held from the library's load to the end of the process; every call on a
+// GPU shares it.  In host code the array's name is only a handle for hipGetSymbolAddress, never an address.
+constexpr size_t kScratchInts = 256 * 1024;   // 1 MiB
+static __device__ __align__(256) int32_t scratch[kScratchInts];
+constexpr int kMaxDevices = 64;
+static int32_t* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch`, per device ordinal
+static std::mutex g_scratch_mutex;
 
 __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __restrict__ idx, int A,
                                                            int E, int32_t* __restrict__ chunk_hist) {
@@ -483,6 +494,28 @@ void launch_permute_variant(const void* x, const int32_t* idx, const float* scor
                            row_of_assign, static_cast<uint8_t*>(x_perm), T, K, row_bytes, r_max);
         if (pad) launch_permute_zero_rows(assign_of_row, x_perm, r_max, row_bytes, s);
     }
+}
+
+size_t permute_scratch_bytes() { return kScratchInts * sizeof(int32_t); }
+
+// Device address of this GPU's copy of `scratch` (looked up once per device, with that device current).
+// Returns nullptr and fills `err` if the runtime refuses.
+int32_t* permute_scratch(hipError_t* err) {
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+    }
+    return g_scratch_ptr[dev];
 }
 
 void launch_permute_zero_rows(const int32_t* assign_of_row, void* x_perm, int rows, int row_bytes, hipStream_t s) {
