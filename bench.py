@@ -28,10 +28,19 @@ PEAK_FP8_TFLOPS = 5000.0    # MI355X dense fp8 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 NSETS = 4                   # rotating activation/workspace sets (defeats the 256 MB Infinity Cache)
 
-# HBM traffic of one gate/up GEMM launch at the default workload, from the
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (bytes);
-# None for workloads that were not profiled.
-MEASURED_TRAFFIC = {"mixtral8x22b": 11.75e9}   # 11.21 GB fetched (L2 misses: HBM + Infinity Cache) + 0.54 GB written
+
+
+def measured_traffic(workload):
+    """Bytes one gate/up GEMM launch moves past the L2 (fetched + written), from the rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE summary of this workload under profiles/ (its line `roofline.traffic gate_up = <bytes>`); None when
+    that workload was not profiled."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic.txt")
+    try:
+        m = re.search(r"^roofline\.traffic gate_up = ([0-9.eE+]+)", open(path).read(), flags=re.M)
+    except OSError:
+        return None
+    return float(m.group(1)) if m else None
 
 
 def parse_args():
@@ -60,6 +69,8 @@ def parse_args():
                     help="also time what ONE GPU of an S-rank expert-parallel group of this workload does between the "
                          "two All-to-All-Vs: gather the received chunks by expert, run its E/S experts, gather back "
                          "by source (every rank holding this workload's token count; no collective is run)")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="moe_set_option knob for sweeps, e.g. gemm_variant=40 (repeatable)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the bare-MFMA probe (what this box sustains on zero and on workload-like operands)")
@@ -117,6 +128,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30, "launches": 5}))
         return
+    for opt in args.option:
+        nm, val = opt.split("=")
+        moe.set_option(nm, int(val))
     cfg = get_config(args.config)
     T, H, E, K, F, Fs = cfg.T, cfg.H, cfg.E, cfg.K, cfg.F, cfg.shared_F
     bf16 = cfg.dtype == "bf16"
@@ -187,6 +201,10 @@ def main():
             s["amax"] = torch.zeros(2, dtype=torch.float32, device="cuda")
         del w["w_gate"], w["w_up"], w["w_down"]
 
+    # shader clock the two expert GEMMs run at: workgroup 0 of each launch leaves its shader-clock and 100 MHz
+    # reference ticks in these cells (the last launch's values are read after the timed region)
+    clk = {nm: torch.zeros(2, dtype=torch.int64, device="cuda") for nm in ("gate_up", "down")}
+
     stage_names = ["router", "permute", "gate_up", "down"] + (["shared"] if Fs else []) + ["combine"]
 
     def step(s, events=None):
@@ -213,9 +231,12 @@ def main():
             moe.permute(s["x"], s["idx"], E, capacity, s["x_perm"], s["counts"], s["offsets"], s["roa"], s["aor"],
                         s["pws"])
             mark(2)
+            moe.gemm_clock_sample(clk["gate_up"])
             moe.expert_gate_up(s["x_perm"], s["offsets"], w["w_gate"], w["w_up"], s["h"])
             mark(3)
+            moe.gemm_clock_sample(clk["down"])
             moe.expert_down(s["h"], s["offsets"], w["w_down"], s["y_perm"])
+            moe.gemm_clock_sample(None)
             mark(4)
             n = 4
         addend = None
@@ -285,13 +306,20 @@ def main():
                          (w_bytes + n * row_bytes) / (PEAK_HBM_GBS * 1e9))
         return round(t * 1e3, 4)
     ges = 1 if fp8 else es   # bytes per GEMM operand element
+    if not fp8:
+        for nm, cell in clk.items():
+            tk = cell.cpu().tolist()
+            if tk[1] > 0:
+                stages[nm]["shader_mhz"] = round(100.0 * tk[0] / tk[1], 0)
     stages["gate_up"]["attainable_ms"] = attainable_ms(4.0 * H * F, 2 * H * F * ges, (H + F) * ges)
     stages["down"]["attainable_ms"] = attainable_ms(2.0 * H * F, H * F * ges, H * es + F * ges)
 
     dom = stages["gate_up"]
     roofline = {"kernel": "gate/up grouped GEMM (moe_expert_gate_up)", "bound": "mfma", "achieved": dom["achieved"],
                 "peak": PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom["frac"],
-                "traffic": None if fp8 else MEASURED_TRAFFIC.get(cfg.name)}
+                "traffic": None if fp8 else measured_traffic(cfg.name)}
+    if "shader_mhz" in dom:
+        roofline["shader_mhz"] = dom["shader_mhz"]
 
     out = {
         "metric": "MoE layer fwd tokens/s; grouped-GEMM % bf16 MFMA peak; permute GB/s % HBM",

@@ -204,13 +204,19 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_r
 // features each, and lane i receives feature i of the four rows).  Both operands are read the same way, so they
 // agree on the order of the contraction values.  Rows past the expert's last one are fetched from the zero row
 // that GU points at (512 bytes of zeros).
-template <int BM, int BN, int WGM, int WGN, int MODE, bool GROUPK = false, bool KMAJ = false, bool IDLE_SKIP = false>
+//
+// DEEP_B: which operand gets the three LDS stages.  false: the activation tile (three stages, fetched two k-tiles
+// ahead) and two stages for the weight tile; true: the other way round -- the weights are what streams in from
+// HBM (every weight byte is used by one M-group only), the activation panels are re-read from the caches.
+template <int BM, int BN, int WGM, int WGN, int MODE, bool GROUPK = false, bool KMAJ = false, bool IDLE_SKIP = false,
+          bool DEEP_B = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, bf16_t* __restrict__ GU,
     int ntn, int ldb, unsigned long long* __restrict__ ticks) {
     static_assert(!GROUPK || MODE == 0, "the weight-gradient form has a plain epilogue");
     static_assert(!KMAJ || (GROUPK && BM == 256 && BN == 256 && WGM * WGN == 8), "row-major form: 256 x 256 tiles, 8 waves");
+    static_assert(!(KMAJ && DEEP_B), "the row-major form keeps three activation stages");
     constexpr bool SWIGLU = MODE == 1 || MODE == 2;
     constexpr int BK = 64;
     constexpr int NW = WGM * WGN;
@@ -222,9 +228,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     constexpr int PA = BM / RPP, PB = BN / RPP;
     constexpr int ROWB = BK * 2;
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
-    constexpr int B_REGION = 3 * A_BYTES;       // three activation slots, then two weight slots
+    constexpr int B_REGION = (DEEP_B ? 2 : 3) * A_BYTES;   // the activation slots, then the weight slots
+    // "early" operand: two slots, fetched one k-tile ahead, issued first in a period; "late" operand: three
+    // slots, fetched two k-tiles ahead
+    constexpr int PE = DEEP_B ? PA : PB, PL = DEEP_B ? PB : PA;
     constexpr int OUTN = SWIGLU ? BN / 2 : BN;
-    constexpr int NLOAD = PA + PB;              // direct loads per thread per k-tile (weights first)
+    constexpr int NLOAD = PA + PB;              // direct loads per thread per k-tile (early operand first)
     constexpr int NREAD = FM + FN;
     constexpr int NMFMA = FM * FN;
     constexpr int NSLOT = NREAD;
@@ -236,11 +245,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     constexpr int FO = SWIGLU ? FN / 2 : FN;
     static_assert(BM % RPP == 0 && BN % RPP == 0 && RPP % 8 == 0, "tile rows must divide into fetch passes");
     static_assert(!SWIGLU || ((BN / 2) % RPP == 0 && FN % 2 == 0), "gate/up halves must be pass- and fragment-aligned");
-    static_assert(LA <= PB, "only weight loads may be issued under k-step 3");
+    static_assert(LA <= PE, "only loads of the early operand may be issued under k-step 3");
     static_assert(LB - LA <= NSLOT && LC - LB <= NSLOT && LA <= NSLOT, "not enough slots for the loads");
-    static_assert(PA < 64, "vmcnt holds 6 bits");
+    static_assert(PL < 64, "vmcnt holds 6 bits");
     static_assert(3 * A_BYTES + 2 * B_BYTES <= 160 * 1024, "tile stages exceed the 160 KiB of LDS");
-    static_assert(NW * 32 * FO * 64 <= A_BYTES, "epilogue patches must fit into one activation slot");
+    static_assert(NW * 32 * FO * 64 <= (DEEP_B ? B_BYTES : A_BYTES), "epilogue patches must fit into one slot of the late operand");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     // clock sample (ticks != NULL): shader-clock and 100 MHz reference ticks workgroup 0 spends in the kernel
@@ -364,14 +373,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         s.rows_left = KMAJ ? (use_cur ? c_krows : n_krows) - k * 64 : 0;
         return s;
     };
-    // load i of a period: i < PB -> pass i of the weight tile (source se, slot
-    // ld_b), else pass i - PB of the activation tile (source sl, slot ld_a)
+    // load i of a period: i < PE -> pass i of the early operand's tile (source se), else pass i - PE of the late
+    // operand's (source sl); ld_b / ld_a: the weight / activation slot being filled
     auto fetch_one = [&](int i, const Src& se, const Src& sl, uint8_t* ld_b, uint8_t* ld_a) {
         if constexpr (KMAJ) {
             if (i < PB)
                 fetch_km(i, se.b0, (uint32_t)ldb * 2u, se.b_lim, se.rows_left, ld_b);
             else
                 fetch_km(i - PB, sl.a, k2, sl.a_lim, sl.rows_left, ld_a);
+        } else if constexpr (DEEP_B) {
+            if (i < PA)
+                fetch_a(i, se.a, se.a_lim, ld_a);
+            else
+                fetch_b(i - PA, sl.b0, sl.b1, sl.b_lim, ld_b);
         } else {
             if (i < PB)
                 fetch_b(i, se.b0, se.b1, se.b_lim, ld_b);
@@ -460,6 +474,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
                 mfma_one(mf_buf, m);
                 ++m;
             }
+            // the k-step's first MFMA waits (lgkmcnt) for the fragments read during the previous k-step; keep
+            // this k-step's reads behind it, or the compiler hoists them and that wait also covers reads issued
+            // a moment ago (a full LDS round trip in front of every k-step)
+            if (slot == 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < 2; ++q)
                 if (rd < NREAD) {
@@ -480,27 +498,38 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     uint8_t* const a_region = smem;
     uint8_t* const b_region = smem + B_REGION;
 
-    // prologue (first tile of this workgroup only): A(0), B(0), then A(1); only
-    // the first two must have landed before the first fragment reads
+    // prologue (first tile of this workgroup only): late(0), early(0), then late(1); only the first two must have
+    // landed before the first fragment reads
     {
         const Src s0 = src(0), s1 = src(1);
 #pragma unroll
-        for (int i = PB; i < NLOAD; ++i) fetch_one(i, s0, s0, b_region, a_region);
+        for (int i = PE; i < NLOAD; ++i) fetch_one(i, s0, s0, b_region, a_region);
 #pragma unroll
-        for (int i = 0; i < PB; ++i) fetch_one(i, s0, s0, b_region, a_region);
+        for (int i = 0; i < PE; ++i) fetch_one(i, s0, s0, b_region, a_region);
 #pragma unroll
-        for (int i = PB; i < NLOAD; ++i) fetch_one(i, s1, s1, b_region, a_region + A_BYTES);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (PA & 0xF) | ((PA >> 4) << 14));  // vmcnt(PA)
+        for (int i = PE; i < NLOAD; ++i)
+            fetch_one(i, s1, s1, b_region + (DEEP_B ? B_BYTES : 0), a_region + (DEEP_B ? 0 : A_BYTES));
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (PL & 0xF) | ((PL >> 4) << 14));  // vmcnt(PL)
         __builtin_amdgcn_s_barrier();
 #pragma unroll
         for (int q = 0; q < NREAD; ++q) read_one(a_region, b_region, 0, 0, q);
-        // head of B(1) into weight slot 1
+        // head of early(1) into the early operand's slot 1
 #pragma unroll
-        for (int i = 0; i < LA; ++i) fetch_one(i, s1, s1, b_region + B_BYTES, a_region);
+        for (int i = 0; i < LA; ++i) fetch_one(i, s1, s1, b_region + B_BYTES, a_region + A_BYTES);
     }
 
-    int l0 = 0, l1 = A_BYTES, l2 = 2 * A_BYTES;  // activation slots of k-tiles kt, kt+1, kt+2
-    int e0 = 0, e1 = B_BYTES;                    // weight slots of k-tiles kt, kt+1
+    // slots of k-tiles kt, kt+1 (, kt+2): three for the late operand, two for the early one
+    int a0 = 0, a1 = A_BYTES, a2 = DEEP_B ? 0 : 2 * A_BYTES;
+    int b0 = 0, b1 = B_BYTES, b2 = DEEP_B ? 2 * B_BYTES : 0;
+    auto rotate = [&]() {
+        if constexpr (DEEP_B) {
+            const int ta = a0; a0 = a1; a1 = ta;
+            const int tb = b0; b0 = b1; b1 = b2; b2 = tb;
+        } else {
+            const int ta = a0; a0 = a1; a1 = a2; a2 = ta;
+            const int tb = b0; b0 = b1; b1 = tb;
+        }
+    };
     for (;;) {
         // (IDLE_SKIP instantiations, chosen for launches with many experts, i.e. many ragged tails; the test costs
         // the plain kernel half a per cent.)  A wave whose rows of the tile all lie past the tile's last valid row
@@ -510,61 +539,50 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         if (!wave_idle) {
         for (int kt = 0; kt < c_kt; ++kt) {
             const Src s1 = src(kt + 1), s2 = src(kt + 2);
-            const uint8_t* ca = a_region + l0;
-            const uint8_t* cb = b_region + e0;
-            uint8_t* lb = b_region + e1;  // B(kt+1)
-            uint8_t* la = a_region + l2;  // A(kt+2)
+            const uint8_t* ca = a_region + a0;
+            const uint8_t* cb = b_region + b0;
+            // this period fills early(kt+1) and late(kt+2)
+            uint8_t* lb = b_region + (DEEP_B ? b2 : b1);
+            uint8_t* la = a_region + (DEEP_B ? a1 : a2);
             __builtin_amdgcn_sched_barrier(0);
             kstep(0, ca, cb, 1, LA, LB, s1, s2, lb, la);  // k-step 0
             kstep(1, ca, cb, 2, LB, LC, s1, s2, lb, la);  // k-step 1
             kstep(0, ca, cb, 3, LC, LC, s1, s2, lb, la);  // k-step 2
-            // B(kt+1) was issued before A(kt+2) in this period and A(kt+1) a period
-            // ago: all but the PA youngest loads must have landed; this wave's
+            // early(kt+1) was issued before late(kt+2) in this period and late(kt+1) a period
+            // ago: all but the PL youngest loads must have landed; this wave's
             // fragment reads of k-tile kt are in registers (lgkmcnt(0))
-            __builtin_amdgcn_s_waitcnt((PA & 0xF) | ((PA >> 4) << 14));
+            __builtin_amdgcn_s_waitcnt((PL & 0xF) | ((PL >> 4) << 14));
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            // k-step 3: first fragments of k-tile kt+1; the weight slot of k-tile
-            // kt is free, the head of B(kt+2) goes into it
-            kstep(1, a_region + l1, b_region + e1, 0, 0, LA, s2, s2, b_region + e0, a_region);
-            const int tl = l0;
-            l0 = l1;
-            l1 = l2;
-            l2 = tl;
-            const int te = e0;
-            e0 = e1;
-            e1 = te;
+            // k-step 3: first fragments of k-tile kt+1; the early operand's slot of k-tile
+            // kt is free, the head of early(kt+2) goes into it
+            kstep(1, a_region + a1, b_region + b1, 0, 0, LA, s2, s2, b_region + b0, a_region + a0);
+            rotate();
         }
         } else {
             for (int kt = 0; kt < c_kt; ++kt) {
                 const Src s1 = src(kt + 1), s2 = src(kt + 2);
-                uint8_t* lb = b_region + e1;
-                uint8_t* la = a_region + l2;
+                uint8_t* lb = b_region + (DEEP_B ? b2 : b1);
+                uint8_t* la = a_region + (DEEP_B ? a1 : a2);
 #pragma unroll
                 for (int i = LA; i < LC; ++i) fetch_one(i, s1, s2, lb, la);
-                __builtin_amdgcn_s_waitcnt((PA & 0xF) | ((PA >> 4) << 14));
+                __builtin_amdgcn_s_waitcnt((PL & 0xF) | ((PL >> 4) << 14));
                 __builtin_amdgcn_s_barrier();
 #pragma unroll
-                for (int i = 0; i < LA; ++i) fetch_one(i, s2, s2, b_region + e0, a_region);
-                const int tl = l0;
-                l0 = l1;
-                l1 = l2;
-                l2 = tl;
-                const int te = e0;
-                e0 = e1;
-                e1 = te;
+                for (int i = 0; i < LA; ++i) fetch_one(i, s2, s2, b_region + b0, a_region + a0);
+                rotate();
             }
             // the next tile may have rows for this wave: its first fragments, as the last k-step would have read them
             if (n_valid) {
 #pragma unroll
-                for (int q = 0; q < NREAD; ++q) read_one(a_region + l0, b_region + e0, 0, 0, q);
+                for (int q = 0; q < NREAD; ++q) read_one(a_region + a0, b_region + b0, 0, 0, q);
             }
         }
-        // Epilogue.  The activation slot that held the last k-tile (now l2) is
+        // Epilogue.  The late operand's slot that held the last k-tile (now its third) is
         // idle: every wave finished reading it before the last barrier, and the
         // next loads into it are issued only after the barrier below.
         store_tile_staged<FM, FN, WM, MODE, (FM * FN * 16 > 128)>(acc, c_row0, c_rows, c_n0, C, GU, N, wm, wn, lane,
-                                              a_region + l2 + wave * (32 * FO * 64));
+                                              (DEEP_B ? b_region + b2 : a_region + a2) + wave * (32 * FO * 64));
         if (!n_valid) break;
         c_a = n_a; c_b0 = n_b0; c_b1 = n_b1; c_alim = n_alim; c_blim = n_blim;
         c_row0 = n_row0; c_rows = n_rows; c_n0 = n_n0;
@@ -588,7 +606,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE>
+template <int BM, int BN, int WGM, int WGN, int MODE, bool DEEP_B = false>
 void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B0,
                     const void* B1, void* C, void* GU, hipStream_t s) {
     constexpr int OUTN = (MODE == 1 || MODE == 2) ? BN / 2 : BN;
@@ -596,8 +614,8 @@ void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int
     const int ntn = (N + OUTN - 1) / OUTN;
     // many experts = many ragged tail tiles: the instantiation whose idle waves skip the multiplication
     const bool idle_skip = MODE != 3 && persist_idle_skip(E);
-    auto kern = idle_skip ? gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, (MODE != 3)>
-                          : gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE>;
+    auto kern = idle_skip ? gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, (MODE != 3), DEEP_B>
+                          : gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, false, DEEP_B>;
     static bool attr_set[2] = {false, false};
     if (!attr_set[idle_skip]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -662,12 +680,12 @@ void launch_persist_groupk_rowmajor(const void* A, int lda, const void* B, int l
                        static_cast<bf16_t*>(const_cast<void*>(zero_row)), M, ldb, g_persist_ticks);
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, bool DEEP_B = false>
 void run_persist_pair(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                       const void* w_gate, const void* w_up, const void* w_down, void* h, void* y_perm, int phase,
                       hipStream_t s) {
-    if (phase & 1) launch_persist<BM, BN, WGM, WGN, 1>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, nullptr, s);
-    if (phase & 2) launch_persist<BM, BN, WGM, WGN, 0>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, nullptr, s);
+    if (phase & 1) launch_persist<BM, BN, WGM, WGN, 1, DEEP_B>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, nullptr, s);
+    if (phase & 2) launch_persist<BM, BN, WGM, WGN, 0, DEEP_B>(h, offsets, r_max, E, H, F, w_down, nullptr, y_perm, nullptr, s);
 }
 
 }  // namespace
@@ -722,6 +740,8 @@ bool launch_persist_ffn(const void* x_perm, const int32_t* offsets, int r_max, i
     switch (variant) {
         case 40: run_persist_pair<256, 256, 2, 2>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         case 41: run_persist_pair<256, 256, 2, 4>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 42: run_persist_pair<256, 256, 2, 2, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
+        case 43: run_persist_pair<256, 256, 2, 4, true>(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, phase, s); return true;
         default: return false;
     }
 }

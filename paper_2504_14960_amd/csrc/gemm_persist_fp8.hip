@@ -292,6 +292,8 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
 #pragma unroll
         for (int slot = 0; slot < NSLOT; ++slot) {
             mfma_one(mf_buf, slot);
+            // the first MFMA waits for the previous k-step's fragment reads only: keep the new reads behind it
+            if (slot == 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < 2; ++q)
                 if (rd < NREAD) {

@@ -209,6 +209,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
                 mfma_one(mf_buf, m);
                 ++m;
             }
+            // the first MFMA waits for the previous k-step's fragment reads only: keep the new reads behind it
+            if (slot == 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < 2; ++q)
                 if (rd < NREAD) {

@@ -8,7 +8,7 @@ from helpers import assert_close, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
-ALL_VARIANTS = [0, 30, 31, 40, 41, 99]
+ALL_VARIANTS = [0, 30, 31, 40, 41, 42, 43, 99]
 
 
 def _offsets(counts):
@@ -58,7 +58,7 @@ def test_every_kernel_variant_on_ragged_experts(ragged_case, variant):
     assert_close(y, y_ref, True, f"y_perm (variant {variant})")
 
 
-@pytest.mark.parametrize("variant", [0, 30, 31, 40, 41])
+@pytest.mark.parametrize("variant", [0, 30, 31, 40, 41, 42, 43])
 def test_deep_contraction_and_fine_grained_experts(variant):
     # long K loops (many k-tiles) and many small experts
     inp, x_perm, offsets, h_ref, y_ref = _case(H=1536, F=128, E=3, counts=[130, 257, 40], seed=4100)
@@ -73,7 +73,7 @@ def test_deep_contraction_and_fine_grained_experts(variant):
     assert_close(y, y_ref, True, "y fine-grained")
 
 
-@pytest.mark.parametrize("variant", [0, 30, 31, 40, 41])
+@pytest.mark.parametrize("variant", [0, 30, 31, 40, 41, 42, 43])
 def test_experts_with_more_m_tiles_than_one_scheduler_group(variant):
     # 2400 rows = 10 (or 19) M-tiles: the scheduler cuts them into balanced groups
     inp, x_perm, offsets, h_ref, y_ref = _case(H=128, F=128, E=3, counts=[2400, 130, 4500], seed=4150)
@@ -82,7 +82,7 @@ def test_experts_with_more_m_tiles_than_one_scheduler_group(variant):
     assert_close(y, y_ref, True, "y many tiles")
 
 
-@pytest.mark.parametrize("variant", [40, 41])
+@pytest.mark.parametrize("variant", [40, 41, 42, 43])
 @pytest.mark.parametrize("workgroups", [8, 24, 13, 64])
 def test_persistent_kernel_walks_many_tiles_per_workgroup(ragged_case, variant, workgroups):
     # few workgroups => each one streams through several tiles (tile boundaries,
@@ -98,7 +98,7 @@ def test_persistent_kernel_walks_many_tiles_per_workgroup(ragged_case, variant, 
     assert_close(y, y_ref, True, f"y_perm (variant {variant}, {workgroups} workgroups)")
 
 
-@pytest.mark.parametrize("variant", [40, 41])
+@pytest.mark.parametrize("variant", [40, 41, 42, 43])
 @pytest.mark.parametrize("idle_skip", [0, 1])
 def test_waves_without_valid_rows_may_skip_their_multiplications(variant, idle_skip):
     # experts whose last tile holds at most 128 rows (half of the waves idle), exactly 128, one row, and full tiles
