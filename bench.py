@@ -81,6 +81,56 @@ def parse_args():
     return ap.parse_args()
 
 
+class PowerSampler:
+    """Average board power over a region, from the amdgpu hwmon file (microwatts), read by a host thread every
+    couple of milliseconds; reports None where the file is not readable."""
+
+    def __init__(self):
+        import glob
+        self.path = None
+        for pat in ("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input",
+                    "/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"):
+            for f in sorted(glob.glob(pat)):
+                try:
+                    int(open(f).read())
+                    self.path = f
+                    break
+                except (OSError, ValueError):
+                    pass
+            if self.path:
+                break
+        self.samples = []
+        self._stop = None
+        self._thread = None
+
+    def start(self):
+        import threading
+        self.samples = []
+        if self.path is None:
+            return
+        self._stop = threading.Event()
+
+        def loop():
+            while not self._stop.is_set():
+                try:
+                    self.samples.append(int(open(self.path).read()) * 1e-6)
+                except (OSError, ValueError):
+                    pass
+                time.sleep(0.002)
+        self._thread = threading.Thread(target=loop, daemon=True)
+        self._thread.start()
+
+    def stop(self):
+        if self._thread is not None:
+            self._stop.set()
+            self._thread.join()
+            self._thread = None
+        v = self.samples
+        if len(v) >= 4:
+            v = v[len(v) // 4:]          # the reading lags the load: keep the later three quarters
+        return round(sum(v) / len(v), 0) if v else None
+
+
 def cpu_baseline(inp, capacity, target_s):
     """Time the CPU oracle (as it stands) on the first S tokens of the batch."""
     import numpy as np
@@ -262,12 +312,15 @@ def main():
 
     nev = len(stage_names) + 1
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(nev)] for _ in range(args.steps)]
+    power = PowerSampler()
     torch.cuda.synchronize()
+    power.start()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(sets[i % NSETS], evs[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    step_watts = power.stop()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     per_step = {nm: sorted(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(args.steps))
@@ -320,6 +373,8 @@ def main():
                 "traffic": None if fp8 else measured_traffic(cfg.name)}
     if "shader_mhz" in dom:
         roofline["shader_mhz"] = dom["shader_mhz"]
+    # board power averaged over the timed steps (the two expert GEMMs are ~98 % of a step at the default workload)
+    roofline["board_power_w"] = step_watts
 
     out = {
         "metric": "MoE layer fwd tokens/s; grouped-GEMM % bf16 MFMA peak; permute GB/s % HBM",
@@ -374,13 +429,16 @@ def main():
             run_probe(d_img, iters // 10, nwg, sink, ticks)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            power.start()
             e0.record()
-            run_probe(d_img, iters, nwg, sink, ticks)
+            for _ in range(12):
+                run_probe(d_img, iters, nwg, sink, ticks)
             e1.record()
             torch.cuda.synchronize()
+            watts = power.stop()
             tk = ticks.cpu().tolist()
-            probe[nm] = {"tflops": round(nwg * iters * flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1),
-                         "shader_mhz": round(100.0 * tk[0] / max(tk[1], 1), 0)}
+            probe[nm] = {"tflops": round(12 * nwg * iters * flop / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1),
+                         "shader_mhz": round(100.0 * tk[0] / max(tk[1], 1), 0), "board_power_w": watts}
         probe["note"] = ("bare MFMA + LDS fragment loop of the grouped GEMM, 256 workgroups x 4 waves, no global traffic: "
                          "the rate and clock this box sustains; operands ~N(0,1) x N(0,0.02^2) as in the workload"
                          + (", as E4M3 codes" if fp8 else ""))

@@ -23,6 +23,7 @@
 
 #include "gemm_persist.h"
 
+
 namespace moe {
 
 static int g_persist_workgroups = 0;  // 0: one per compute unit
@@ -242,6 +243,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     constexpr int LA = NLOAD / 3;
     constexpr int LB = LA + (NLOAD - LA + 1) / 2;
     constexpr int LC = NLOAD;
+    // fragment reads per slot of a k-step: one (spread over the whole k-step) with eight waves, whose LDS pipe is
+    // as busy as the matrix pipe; two with four waves
+    constexpr int RDPS = NW == 8 ? 1 : 2;
     constexpr int FO = SWIGLU ? FN / 2 : FN;
     static_assert(BM % RPP == 0 && BN % RPP == 0 && RPP % 8 == 0, "tile rows must divide into fetch passes");
     static_assert(!SWIGLU || ((BN / 2) % RPP == 0 && FN % 2 == 0), "gate/up halves must be pass- and fragment-aligned");
@@ -479,7 +483,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
             // a moment ago (a full LDS round trip in front of every k-step)
             if (slot == 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int q = 0; q < 2; ++q)
+            for (int q = 0; q < RDPS; ++q)
                 if (rd < NREAD) {
                     read_one(rd_a, rd_b, rd_s, mf_buf ^ 1, rd);
                     ++rd;

@@ -138,11 +138,10 @@ bool launch_expert_ffn(const void* x_perm, const int32_t* offsets, int r_max, in
         return true;
     }
     if (variant == 0) {
-        // tuned default (measured on MI355X at the benchmark shapes): the persistent kernel with three LDS stages
-        // for the weight tile, 8 waves for layers with few, large experts and 4 waves (less LDS traffic, more
-        // clock under the power cap) for layers with many; layers too shallow for its k stream fall back to
-        // the one-workgroup-per-tile kernels (8 waves gate/up, 4 waves down)
-        if (launch_persist_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, E >= 16 ? 42 : 43, phase, s))
+        // tuned default (measured on MI355X at the benchmark shapes): the persistent 8-wave kernel with three LDS
+        // stages for the weight tile; layers too shallow for its k stream fall back to the
+        // one-workgroup-per-tile kernels (8 waves gate/up, 4 waves down)
+        if (launch_persist_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 43, phase, s))
             return true;
         bool ok = true;
         if (phase & 1) ok = ok && launch_pipe3_ffn(x_perm, offsets, r_max, H, F, E, w_gate, w_up, w_down, h, y_perm, 31, 1, s);
