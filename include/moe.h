@@ -530,7 +530,10 @@ moe_status_t moe_gemm_clock_sample(uint64_t* ticks);
  * or 4; 0 = chosen from T and E); "wgrad_rowmajor" (1 = the expert FFN's backward
  * forms the weight gradients straight from the row-major activations with
  * transposing LDS loads instead of from transposed copies: about 1.8x slower
- * weight-gradient GEMMs, no ragged transposes; default 0); "gemm_idle_skip" (the
+ * weight-gradient GEMMs, no ragged transposes; default 0); "permute_fused" (1, the default: layers with at most 8 experts and at most
+ * 65532 assignments run moe_permute as ONE kernel in which every workgroup counts
+ * the whole index array itself while its rows are on their way; 0: always the
+ * three-kernel form; 2 / 3 force one / two tokens per wave); "gemm_idle_skip" (the
  * persistent GEMM kernels in which the waves that hold no valid row of a ragged
  * tile skip its multiplications: 1 = always, 0 = never, -1 = for E >= 16, the
  * default). */

@@ -58,6 +58,7 @@ void launch_router_backward(const void* x, const void* w, const float* logits, c
 void set_router_tile(int mb);
 
 size_t permute_workspace_bytes(int T, int K, int E);
+void set_permute_fused(int v);   // 1 (default): small index arrays take the one-launch dispatch; 0: never
 void launch_permute(const void* x, const int32_t* idx, int T, int H, int E, int K, int capacity,
                     int r_max, moe_dtype_t dt, void* x_perm, int32_t* counts, int32_t* offsets,
                     int32_t* row_of_assign, int32_t* assign_of_row, void* ws, hipStream_t s);

@@ -12,6 +12,9 @@
 //                           with wave ballots and writes both maps.
 //   3. permute_copy_kernel  one wave per token: the row is read once with
 //                           16-byte lanes and stored to each kept destination.
+// Layers with few experts and a small index array (the Mixtral shapes) take
+// permute_fused_kernel instead: the same maps from ONE launch, the counting
+// hidden under the latency of the row loads.
 #include <mutex>
 
 #include "fp8_convert.h"
@@ -418,12 +421,201 @@ __global__ __launch_bounds__(256) void permute_copy_fp8_kernel(const uint8_t* __
     }
 }
 
+// ---- all of a2 in one launch, for layers with few experts and an index array small enough that every workgroup can
+// count it itself (E <= 8, T*K <= 32768: the Mixtral shapes) ----
+// A workgroup of 16 waves owns TB = 16 * tpw consecutive tokens (wave w the tokens t0 + w, t0 + w + 16, ...; one
+// workgroup per compute unit at the benchmark shapes).  Every wave first requests
+// the row of its first token (rows do not depend on the maps), then, while that load is in flight, the workgroup counts the WHOLE
+// index array: every thread keeps eight 8-bit counters in one 64-bit register (it sees at most 64 assignments),
+// one for the whole array and one for the assignments before the workgroup's own; the threads' registers are
+// widened to 16-bit fields and added across the workgroup (integer sums: no order dependence).  Totals clamp to
+// the capacity and scan to the offsets; the workgroup's own few assignments are ranked in ascending order with
+// wave ballots; the maps are written and the rows stored.  Same maps, bit for bit, as the three-kernel path: rank = assignments of the same expert
+// with a lower index.  No workgroup waits for another.
+constexpr int kFusedMaxRowVecs = 16;       // row of at most 16 KiB: 16 x 16 bytes per lane
+constexpr int kFusedMaxAssign = 65532;     // <= 64 assignments per thread (8-bit counters), totals below 2^16
+constexpr int kFusedMaxExperts = 8;
+constexpr int kFusedWaves = 16;
+
+// NV: 16-byte pieces per lane of a row (row of at most NV KiB); TPW: tokens per wave, all requested up front
+template <int NV, int TPW>
+__global__ __launch_bounds__(kFusedWaves * 64) void permute_fused_kernel(
+    const uint8_t* __restrict__ x, const int32_t* __restrict__ idx, int T, int K, int E, int capacity, int row_bytes,
+    int r_max, uint8_t* __restrict__ x_perm, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ row_of_assign, int32_t* __restrict__ assign_of_row) {
+    constexpr int NWV = kFusedWaves, NTH = NWV * 64;
+    __shared__ unsigned long long red[NWV][4];
+    __shared__ int base[kFusedMaxExperts];
+    __shared__ int run[kFusedMaxExperts];
+    __shared__ int off[kFusedMaxExperts + 1];
+    __shared__ int rows[NWV * TPW * kFusedMaxExperts];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int A = T * K;
+    constexpr int TB = NWV * TPW;
+    const int t0 = blockIdx.x * TB;
+    const int a0 = t0 * K;                                   // first assignment of this workgroup (a multiple of 4)
+    const int na = min(TB, T - t0) * K;                      // its assignments
+
+    // The index array first, then the rows: loads return in order, so the counting below can start as soon as the
+    // (cached) indices are back while the rows are still on their way from memory.
+    constexpr int NPRE = 4;                                  // index groups per thread requested up front
+    const int ngroups = A >> 2;
+    const int4* idx4 = reinterpret_cast<const int4*>(idx);
+    int4 pre[NPRE];
+#pragma unroll
+    for (int q = 0; q < NPRE; ++q) {
+        const int g = tid + q * NTH;
+        pre[q] = (g < ngroups) ? idx4[g] : int4{-1, -1, -1, -1};
+    }
+    // phase 0: the row of this wave's first token (rows do not depend on the maps)
+    const bool copy = x != nullptr;
+    u32x4 v[TPW][NV];
+    if (copy) {
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+            const int t = t0 + j * NWV + wave;
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+                if (t < T && i * 1024 + lane * 16 < row_bytes)
+                    v[j][i] = *reinterpret_cast<const u32x4*>(x + (size_t)t * row_bytes + i * 1024 + lane * 16);
+        }
+    }
+    if (tid < kFusedMaxExperts) run[tid] = 0;
+
+    // phase 1: per-expert totals over all assignments and over those before a0, eight 8-bit counters per register
+    unsigned long long tot8 = 0, base8 = 0;
+    auto field = [&](int e) -> unsigned long long { return ((unsigned)e < (unsigned)E) ? 1ull << (8 * e) : 0ull; };
+    {
+#pragma unroll
+        for (int q = 0; q < NPRE; ++q) {
+            const int g = tid + q * NTH;
+            const unsigned long long inc = field(pre[q].x) + field(pre[q].y) + field(pre[q].z) + field(pre[q].w);
+            tot8 += inc;
+            if (4 * g < a0) base8 += inc;                    // a0 is a multiple of 4: a group never straddles it
+        }
+        for (int g = tid + NPRE * NTH; g < ngroups; g += NTH) {
+            const int4 e4 = idx4[g];
+            const unsigned long long inc = field(e4.x) + field(e4.y) + field(e4.z) + field(e4.w);
+            tot8 += inc;
+            if (4 * g < a0) base8 += inc;
+        }
+        const int a = (ngroups << 2) + tid;                  // the last A mod 4 assignments
+        if (tid < 4 && a < A) {
+            const unsigned long long inc = field(idx[a]);
+            tot8 += inc;
+            if (a < a0) base8 += inc;
+        }
+    }
+    // 16-bit fields (even experts, odd experts), added over the wave, then over the waves
+    const unsigned long long M = 0x00FF00FF00FF00FFull;
+    unsigned long long s4[4] = {tot8 & M, (tot8 >> 8) & M, base8 & M, (base8 >> 8) & M};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) {
+            const uint32_t lo = __shfl_xor((uint32_t)s4[q], d, 64);
+            const uint32_t hi = __shfl_xor((uint32_t)(s4[q] >> 32), d, 64);
+            s4[q] += ((unsigned long long)hi << 32) | lo;
+        }
+        if (lane == 0) red[wave][q] = s4[q];
+    }
+    __syncthreads();
+    // phase 2: every thread holds all totals; thread 0 scans them
+    if (tid < kFusedMaxExperts) {
+        const int e = tid;
+        const int q = e & 1, sh = 16 * (e >> 1);
+        unsigned long long tsum = 0, bsum = 0;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) {
+            tsum += red[w][q];
+            bsum += red[w][2 + q];
+        }
+        const int tot_e = (e < E) ? (int)((tsum >> sh) & 0xFFFFu) : 0;
+        base[e] = (int)((bsum >> sh) & 0xFFFFu);
+        const int cnt = (capacity > 0 && tot_e > capacity) ? capacity : tot_e;
+        // inclusive prefix over the eight lanes
+        int incl = cnt;
+#pragma unroll
+        for (int d = 1; d < kFusedMaxExperts; d <<= 1) {
+            const int o = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += o;
+        }
+        off[e + 1] = incl;
+        if (e == 0) off[0] = 0;
+        if (blockIdx.x == 0 && e < E) {
+            counts[e] = cnt;
+            offsets[e + 1] = incl;
+            if (e == 0) offsets[0] = 0;
+        }
+    }
+    __syncthreads();
+
+    // phase 3: this workgroup's own assignments, unit by unit in ascending order (wave 0; at most 512)
+    int nbits = 0;
+    while ((1 << nbits) < E) ++nbits;
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    if (wave == 0) {
+        for (int u0 = 0; u0 < na; u0 += 64) {
+            const int a = a0 + u0 + lane;
+            int e = (u0 + lane < na) ? idx[a] : -1;
+            const bool valid = (unsigned)e < (unsigned)E;
+            // lanes of this unit that name the same expert: one ballot per bit of the expert index
+            uint64_t peers = __ballot(valid);
+            for (int b = 0; b < nbits; ++b) {   // uniform trip count
+                const bool bit = (e >> b) & 1;
+                const uint64_t m = __ballot(valid && bit);
+                peers &= bit ? m : ~m;
+            }
+            int row = -1;
+            if (valid) {
+                const int before_unit = run[e];                                  // earlier units of this workgroup
+                const int rank = base[e] + before_unit + __popcll(peers & lt_mask);
+                if (capacity <= 0 || rank < capacity) row = off[e] + rank;
+                if (row >= r_max) row = -1;  // cannot happen for a consistent r_max; never an address
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");           // every lane has read run[e]
+                if ((peers & lt_mask) == 0) run[e] = before_unit + __popcll(peers);
+            }
+            if (u0 + lane < na) {
+                rows[u0 + lane] = row;
+                row_of_assign[a] = row;
+                if (row >= 0) assign_of_row[row] = a;
+            }
+        }
+    }
+    // rows past the kept total are marked unused
+    {
+        const int R = off[E];
+        for (int r = R + blockIdx.x * NTH + tid; r < r_max; r += gridDim.x * NTH) assign_of_row[r] = -1;
+    }
+    __syncthreads();
+
+    // phase 4: every row to each of its kept destinations 
+    if (copy) {
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+            const int lt = j * NWV + wave;
+            if (t0 + lt >= T) continue;
+            for (int k = 0; k < K; ++k) {
+                const int row = rows[lt * K + k];                                  // wave-uniform
+                if (row < 0) continue;
+                uint8_t* dst = x_perm + (size_t)row * row_bytes + lane * 16;
+#pragma unroll
+                for (int i = 0; i < NV; ++i)
+                    if (i * 1024 + lane * 16 < row_bytes) *reinterpret_cast<u32x4*>(dst + i * 1024) = v[j][i];
+            }
+        }
+    }
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v0, int32_t step) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v0 + i * step;
 }
 
 }  // namespace
+
+static int g_permute_fused = 1;   // 0: always the three-kernel path
+void set_permute_fused(int v) { g_permute_fused = v; }   // 2 / 3: force one / two tokens per wave (experiments)
 
 size_t permute_workspace_bytes(int T, int K, int E) {
     const long long A = (long long)T * K;
@@ -435,6 +627,27 @@ void launch_permute(const void* x, const int32_t* idx, int T, int H, int E, int 
                     int r_max, moe_dtype_t dt, void* x_perm, int32_t* counts, int32_t* offsets,
                     int32_t* row_of_assign, int32_t* assign_of_row, void* ws, hipStream_t s) {
     const int A = T * K;
+    const int row_bytes_all = H * (dt == MOE_BF16 ? 2 : 4);
+    if (g_permute_fused && E <= kFusedMaxExperts && A <= kFusedMaxAssign && row_bytes_all <= kFusedMaxRowVecs * 1024 &&
+        row_bytes_all % 16 == 0) {
+        // few experts, small index array: one launch (the workspace is not used)
+        const uint8_t* xs = (x != nullptr && x_perm != nullptr) ? static_cast<const uint8_t*>(x) : nullptr;
+        // two tokens per wave (one round of workgroups at T = 8192) where both rows fit into the registers of a
+        // 16-wave workgroup, else one
+        const int nv = (row_bytes_all + 1023) / 1024;
+        const bool two = (g_permute_fused == 1 && nv <= 12 && T > kFusedWaves * 256) || g_permute_fused == 3;
+#define FUSED_CASE(NVV, TPWW)                                                                                           \
+    hipLaunchKernelGGL((permute_fused_kernel<NVV, TPWW>), dim3((T + kFusedWaves * TPWW - 1) / (kFusedWaves * TPWW)),     \
+                       dim3(kFusedWaves * 64), 0, s, xs, idx, T, K, E, capacity, row_bytes_all, r_max,                   \
+                       static_cast<uint8_t*>(x_perm), counts, offsets, row_of_assign, assign_of_row)
+        if (two && nv <= 12) {
+            if (nv <= 4) FUSED_CASE(4, 2); else if (nv <= 8) FUSED_CASE(8, 2); else FUSED_CASE(12, 2);
+        } else {
+            if (nv <= 4) FUSED_CASE(4, 1); else if (nv <= 8) FUSED_CASE(8, 1); else if (nv <= 12) FUSED_CASE(12, 1); else FUSED_CASE(16, 1);
+        }
+#undef FUSED_CASE
+        return;
+    }
     const int nchunks = (A + kChunk - 1) / kChunk;
     int32_t* chunk_hist = static_cast<int32_t*>(ws);
     hipLaunchKernelGGL(permute_hist_kernel, dim3(nchunks), dim3(256), 0, s, idx, A, E, chunk_hist);

@@ -23,7 +23,7 @@ def test_noalloc_permute_equals_permute_on_two_calls_in_a_row():
     import paper_2504_14960_amd as moe
     rng = np.random.default_rng(77)
     # (T, H, E, K, capacity): a large skewed call with drops first, then a much smaller dropless one
-    for T, H, E, K, capacity in [(20000, 256, 64, 6, 1500), (700, 128, 8, 2, 0)]:
+    for T, H, E, K, capacity in [(20000, 256, 64, 6, 1500), (700, 128, 16, 2, 0)]:
         print(f"moe_permute_noalloc T={T} H={H} E={E} K={K} capacity={capacity}", flush=True)
         p = 1.0 / np.arange(1, E + 1) ** 1.2
         idx = np.stack([rng.choice(E, size=K, replace=False, p=p / p.sum()) for _ in range(T)]).astype(np.int32)
