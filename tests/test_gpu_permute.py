@@ -131,3 +131,37 @@ def test_round_trip_with_identity_experts_returns_x():
             np.testing.assert_array_equal(y, x)
         else:
             assert_close(y, values(x), True, "round trip")
+
+
+@pytest.mark.parametrize("fused", [0, 1, 2, 3], ids=["three_kernels", "one_launch", "one_token_per_wave", "two_tokens_per_wave"])
+@pytest.mark.parametrize("T,H,E,K,capacity,kind,bf16", [
+    (8192, 64, 8, 2, 0, "normal", True),          # the benchmark's index array (rows kept small for the oracle)
+    (8192, 64, 8, 2, 1800, "onehot", True),       # with drops
+    (4099, 24, 8, 3, 0, "normal", True),          # T*K odd: the last assignments are not a group of four
+    (333, 6144, 7, 2, 0, "normal", True),         # 12 KiB rows, E not a power of two, ragged last workgroup
+    (50, 8192, 8, 1, 0, "normal", True),          # 16 KiB rows: one token per wave whatever is asked
+    (700, 100, 3, 3, 200, "normal", False),       # fp32 rows of 400 bytes, K = E, capacity
+    (32766, 8, 2, 2, 0, "normal", True),          # 65532 assignments: the largest index array the one launch takes
+    (16400, 16, 8, 4, 0, "onehot", True),         # 65600 assignments: always three kernels
+    (17, 8, 8, 8, 1, "normal", True),             # capacity 1, every expert on every token
+])
+def test_one_launch_and_three_kernel_dispatch_agree_with_the_oracle(T, H, E, K, capacity, kind, bf16, fused):
+    """Layers with at most 8 experts take a dispatch that is ONE kernel (every workgroup counts the index array
+    itself); it must give the oracle's maps bit for bit like the three-kernel form, at every token-per-wave setting."""
+    import paper_2504_14960_amd as moe
+    idx, _ = _idx(900 + T + K, T, E, K, kind)
+    idx = idx.copy()
+    idx[5 % T, 0] = E            # an index outside [0, E): a dropped assignment
+    x = make_tokens(901, T, H, bf16=bf16)
+    want = oracle.permute(x, idx, E, capacity)
+    moe.set_option("permute_fused", fused)
+    try:
+        x_perm, counts, offsets, roa, aor = _gpu_permute(x, idx, E, capacity)
+    finally:
+        moe.set_option("permute_fused", 1)
+    np.testing.assert_array_equal(counts, want.counts)
+    np.testing.assert_array_equal(offsets, want.offsets)
+    np.testing.assert_array_equal(roa, want.row_of_assign)
+    np.testing.assert_array_equal(aor, want.assign_of_row)
+    np.testing.assert_array_equal(x_perm[:want.R], want.x_perm[:want.R])
+    assert (x_perm[want.R:] == 0).all(), "rows past the kept total must be left untouched"

@@ -76,3 +76,31 @@ def test_router_fp32_tiny_config():
     assert np.abs(logits - l64).max() <= 1e-5
     np.testing.assert_array_equal(idx, want_idx)
     np.testing.assert_allclose(gate, want_gate, rtol=GATE_RTOL, atol=1e-5)
+
+
+@pytest.mark.parametrize("tile", [1, 2, 4])
+@pytest.mark.parametrize("T,H,E,K,bias,renorm", [
+    (1000, 512, 8, 2, "normal", True),      # ragged last tile
+    (777, 1032, 64, 8, None, False),        # a ragged last slice
+    (333, 264, 5, 3, "normal", True),       # fewer slices than waves
+    (260, 96, 20, 4, None, False),          # two expert blocks
+    (4100, 6144, 8, 2, "normal", True),     # the benchmark's row length
+    (130, 40, 40, 7, None, True),           # three expert blocks
+])
+def test_every_router_tile_height_against_oracle(T, H, E, K, bias, renorm, tile):
+    """The router kernel at every tile height (16, 32, 64 tokens per workgroup) on shapes with ragged tiles, rows
+    and expert blocks: logits, indices and gates."""
+    import paper_2504_14960_amd as moe
+    cfg = get_config("mixtral8x7b").scaled(T=T, H=H, E=E, K=K, bias=bias, seed=2100 + E)
+    inp = make_layer_inputs(cfg, ["x", "w_router", "bias"])
+    guard_margins(inp, K)
+    l64 = oracle.router_logits(inp["x"], inp["w_router"], inp.bias)
+    want_idx, want_gate = oracle.topk_gates(l64.astype(np.float32), K, renorm)
+    moe.set_option("router_tile", tile)
+    try:
+        logits, idx, gate = _gpu_topk(np.zeros((T, E), np.float32), K, renorm, inp["x"], inp["w_router"], inp.bias)
+    finally:
+        moe.set_option("router_tile", 0)
+    assert np.abs(logits - l64).max() <= LOGIT_ATOL
+    np.testing.assert_array_equal(idx, want_idx)
+    np.testing.assert_allclose(gate, want_gate, rtol=GATE_RTOL, atol=2e-5)
