@@ -704,7 +704,7 @@ bool persist_idle_skip(int E) { return g_persist_idle_skip < 0 ? E >= 16 : g_per
 bool launch_grouped_nt(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B,
                        void* C, hipStream_t s) {
     if (K < 128 || K % 64 || N % 8) return false;
-    launch_persist<256, 256, 2, 4, 0>(A, offsets, r_max, E, N, K, B, nullptr, C, nullptr, s);
+    launch_persist<256, 256, 2, 4, 0, true>(A, offsets, r_max, E, N, K, B, nullptr, C, nullptr, s);
     return true;
 }
 
@@ -725,7 +725,7 @@ void launch_persist_wgrad_rowmajor(const void* a, int lda, const void* b, int ld
 bool launch_grouped_nt_swiglu_bwd(const void* A, const int32_t* offsets, int r_max, int E, int N, int K,
                                   const void* B, const void* gu, void* dgdu, hipStream_t s) {
     if (K < 128 || K % 64 || N % 8) return false;
-    launch_persist<256, 256, 2, 4, 3>(A, offsets, r_max, E, N, K, B, nullptr, dgdu, const_cast<void*>(gu), s);
+    launch_persist<256, 256, 2, 4, 3, true>(A, offsets, r_max, E, N, K, B, nullptr, dgdu, const_cast<void*>(gu), s);
     return true;
 }
 
@@ -733,7 +733,7 @@ bool launch_grouped_nt_swiglu_bwd(const void* A, const int32_t* offsets, int r_m
 bool launch_gate_up_saving(const void* x_perm, const int32_t* offsets, int r_max, int H, int F, int E,
                            const void* w_gate, const void* w_up, void* h, void* gu, hipStream_t s) {
     if (H < 128 || H % 64 || F % 8) return false;
-    launch_persist<256, 256, 2, 4, 2>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, gu, s);
+    launch_persist<256, 256, 2, 4, 2, true>(x_perm, offsets, r_max, E, F, H, w_gate, w_up, h, gu, s);
     return true;
 }
 
