@@ -906,6 +906,10 @@ moe_status_t moe_set_option(const char* name, int value) {
         moe::set_persist_idle_skip(value < 0 ? -1 : (value != 0));
         return MOE_OK;
     }
+    if (name && strcmp(name, "fp8_deep_weights") == 0) {
+        moe::set_fp8_deep_b(value);
+        return MOE_OK;
+    }
     if (name && strcmp(name, "permute_fused") == 0) {
         moe::set_permute_fused(value);
         return MOE_OK;

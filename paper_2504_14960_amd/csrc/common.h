@@ -147,6 +147,7 @@ void launch_probe_mfma_fp8(const void* image, int iters, int workgroups, float* 
 void launch_fp8_quantize(const void* src, moe_dtype_t dt, size_t n, float scale, void* dst, float* amax,
                          hipStream_t s);
 bool fp8_ffn_supported(int H, int F);
+void set_fp8_deep_b(int v);   // FP8 grouped GEMM: 1 (default) three LDS stages for the weight tile, 0 for the activation tile
 void launch_permute_fp8(const void* x, const int32_t* idx, int T, int H, int E, int K, int capacity, int r_max,
                         float scale, void* x_perm_fp8, int32_t* counts, int32_t* offsets, int32_t* row_of_assign,
                         int32_t* assign_of_row, float* amax, void* ws, hipStream_t s);

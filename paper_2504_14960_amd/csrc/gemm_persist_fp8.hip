@@ -128,7 +128,8 @@ __device__ __forceinline__ void store_y_bf16(f32x16 (&acc)[FM][FN], int t_row0, 
 // A [rows, K] E4M3, B0/B1 [E, N, K] E4M3 (SWIGLU: gate and up), K a multiple of
 // 128.  SWIGLU: C is h [rows, N] E4M3, s0/s1 dequantise g/u, s2 scales h, amax
 // receives max |h|.  Otherwise C is y [rows, N] bf16 and s0 dequantises it.
-template <bool SWIGLU, bool IDLE_SKIP = false>
+// DEEP_B: the weight tile, not the activation tile, gets the three LDS stages (see gemm_persist.hip).
+template <bool SWIGLU, bool IDLE_SKIP = false, bool DEEP_B = false>
 __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
     const uint8_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const uint8_t* __restrict__ B0, const uint8_t* __restrict__ B1, void* __restrict__ C, int ntn, float s0,
@@ -143,7 +144,9 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
     constexpr int RPP = NT / CPR;
     constexpr int PA = BM / RPP, PB = BN / RPP;
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
-    constexpr int B_REGION = 3 * A_BYTES;
+    constexpr int B_REGION = (DEEP_B ? 2 : 3) * A_BYTES;
+    // "early" operand: two slots, fetched one k-tile ahead, issued first in a period; "late": three slots
+    constexpr int PE = DEEP_B ? PA : PB, PL = DEEP_B ? PB : PA;
     constexpr int OUTN = SWIGLU ? BN / 2 : BN;
     constexpr int NLOAD = PA + PB;
     constexpr int NREAD = 2 * (FM + FN);        // 16-byte LDS reads per k-step: two per fragment
@@ -152,9 +155,9 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
     // a period's loads: the head of the weight tile under k-step 1 of the previous
     // k-tile (after the barrier), the rest and the activation tile under k-step 0
     constexpr int LA = NLOAD / 3;
-    static_assert(LA <= PB && NLOAD - LA <= NSLOT && LA <= NSLOT && NREAD <= 2 * NSLOT, "slots");
+    static_assert(LA <= PE && NLOAD - LA <= NSLOT && LA <= NSLOT && NREAD <= 2 * NSLOT, "slots");
     static_assert(3 * A_BYTES + 2 * B_BYTES <= 160 * 1024, "tile stages exceed the 160 KiB of LDS");
-    static_assert(NW * 32 * (FN * 64) <= A_BYTES, "epilogue patches must fit into one activation slot");
+    static_assert(NW * 32 * (FN * 64) <= (DEEP_B ? B_BYTES : A_BYTES), "epilogue patches must fit into one slot of the late operand");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -223,11 +226,19 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
         s.b_lim = use_cur ? c_blim : n_blim;
         return s;
     };
+    // load i of a period: the early operand's passes first (source se), then the late operand's (source sl)
     auto fetch_one = [&](int i, const Src& se, const Src& sl, uint8_t* ld_b, uint8_t* ld_a) {
-        if (i < PB)
-            fetch_b(i, se.b0, se.b1, se.b_lim, ld_b);
-        else
-            fetch_a(i - PB, sl.a, sl.a_lim, ld_a);
+        if constexpr (DEEP_B) {
+            if (i < PA)
+                fetch_a(i, se.a, se.a_lim, ld_a);
+            else
+                fetch_b(i - PA, sl.b0, sl.b1, sl.b_lim, ld_b);
+        } else {
+            if (i < PB)
+                fetch_b(i, se.b0, se.b1, se.b_lim, ld_b);
+            else
+                fetch_a(i - PB, sl.a, sl.a_lim, ld_a);
+        }
     };
 
     const int fr = lane & 31, fk = lane >> 5;
@@ -311,24 +322,36 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
     uint8_t* const a_region = smem;
     uint8_t* const b_region = smem + B_REGION;
     {
+        // late(0), early(0), late(1); the first two must have landed before the first fragment reads
         const Src q0 = src(0), q1 = src(1);
 #pragma unroll
-        for (int i = PB; i < NLOAD; ++i) fetch_one(i, q0, q0, b_region, a_region);
+        for (int i = PE; i < NLOAD; ++i) fetch_one(i, q0, q0, b_region, a_region);
 #pragma unroll
-        for (int i = 0; i < PB; ++i) fetch_one(i, q0, q0, b_region, a_region);
+        for (int i = 0; i < PE; ++i) fetch_one(i, q0, q0, b_region, a_region);
 #pragma unroll
-        for (int i = PB; i < NLOAD; ++i) fetch_one(i, q1, q1, b_region, a_region + A_BYTES);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (PA & 0xF) | ((PA >> 4) << 14));  // vmcnt(PA)
+        for (int i = PE; i < NLOAD; ++i)
+            fetch_one(i, q1, q1, b_region + (DEEP_B ? B_BYTES : 0), a_region + (DEEP_B ? 0 : A_BYTES));
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (PL & 0xF) | ((PL >> 4) << 14));  // vmcnt(PL)
         __builtin_amdgcn_s_barrier();
 #pragma unroll
         for (int r = 0; r < NREAD; ++r) read_one(a_region, b_region, 0, 0, r);
 #pragma unroll
-        for (int i = 0; i < LA; ++i) fetch_one(i, q1, q1, b_region + B_BYTES, a_region);
+        for (int i = 0; i < LA; ++i) fetch_one(i, q1, q1, b_region + B_BYTES, a_region + A_BYTES);
     }
 
     float amax = 0.f;
-    int l0 = 0, l1 = A_BYTES, l2 = 2 * A_BYTES;
-    int e0 = 0, e1 = B_BYTES;
+    // slots of k-tiles kt, kt+1 (, kt+2): three for the late operand, two for the early one
+    int a0 = 0, a1 = A_BYTES, a2 = DEEP_B ? 0 : 2 * A_BYTES;
+    int b0 = 0, b1 = B_BYTES, b2 = DEEP_B ? 2 * B_BYTES : 0;
+    auto rotate = [&]() {
+        if constexpr (DEEP_B) {
+            const int ta = a0; a0 = a1; a1 = ta;
+            const int tb = b0; b0 = b1; b1 = b2; b2 = tb;
+        } else {
+            const int ta = a0; a0 = a1; a1 = a2; a2 = ta;
+            const int tb = b0; b0 = b1; b1 = tb;
+        }
+    };
     for (;;) {
         // IDLE_SKIP (launches with many experts): a wave whose rows of the tile all lie past its last valid row
         // only issues its share of the loads and meets the barriers (see gemm_persist.hip)
@@ -337,46 +360,36 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
         for (int kt = 0; kt < KT; ++kt) {
             const Src q1 = src(kt + 1), q2 = src(kt + 2);
             __builtin_amdgcn_sched_barrier(0);
-            // k-step 0: rest of B(kt+1), all of A(kt+2)
-            kstep(0, a_region + l0, b_region + e0, 1, LA, NLOAD, q1, q2, b_region + e1, a_region + l2);
-            // all but the PA youngest loads (those of A(kt+2)) have landed; this
+            // k-step 0: rest of early(kt+1), all of late(kt+2)
+            kstep(0, a_region + a0, b_region + b0, 1, LA, NLOAD, q1, q2, b_region + (DEEP_B ? b2 : b1),
+                  a_region + (DEEP_B ? a1 : a2));
+            // all but the PL youngest loads (those of late(kt+2)) have landed; this
             // wave's fragment reads of k-tile kt are in registers
-            __builtin_amdgcn_s_waitcnt((PA & 0xF) | ((PA >> 4) << 14));
+            __builtin_amdgcn_s_waitcnt((PL & 0xF) | ((PL >> 4) << 14));
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            // k-step 1: first fragments of k-tile kt+1, head of B(kt+2) into the freed weight slot
-            kstep(1, a_region + l1, b_region + e1, 0, 0, LA, q2, q2, b_region + e0, a_region);
-            const int tl = l0;
-            l0 = l1;
-            l1 = l2;
-            l2 = tl;
-            const int te = e0;
-            e0 = e1;
-            e1 = te;
+            // k-step 1: first fragments of k-tile kt+1, head of early(kt+2) into the freed slot
+            kstep(1, a_region + a1, b_region + b1, 0, 0, LA, q2, q2, b_region + b0, a_region + a0);
+            rotate();
         }
         } else {
             for (int kt = 0; kt < KT; ++kt) {
                 const Src q1 = src(kt + 1), q2 = src(kt + 2);
 #pragma unroll
-                for (int i = LA; i < NLOAD; ++i) fetch_one(i, q1, q2, b_region + e1, a_region + l2);
-                __builtin_amdgcn_s_waitcnt((PA & 0xF) | ((PA >> 4) << 14));
+                for (int i = LA; i < NLOAD; ++i)
+                    fetch_one(i, q1, q2, b_region + (DEEP_B ? b2 : b1), a_region + (DEEP_B ? a1 : a2));
+                __builtin_amdgcn_s_waitcnt((PL & 0xF) | ((PL >> 4) << 14));
                 __builtin_amdgcn_s_barrier();
 #pragma unroll
-                for (int i = 0; i < LA; ++i) fetch_one(i, q2, q2, b_region + e0, a_region);
-                const int tl = l0;
-                l0 = l1;
-                l1 = l2;
-                l2 = tl;
-                const int te = e0;
-                e0 = e1;
-                e1 = te;
+                for (int i = 0; i < LA; ++i) fetch_one(i, q2, q2, b_region + b0, a_region + a0);
+                rotate();
             }
             if (n_valid) {   // the next tile may have rows for this wave: its first fragments
 #pragma unroll
-                for (int r = 0; r < NREAD; ++r) read_one(a_region + l0, b_region + e0, 0, 0, r);
+                for (int r = 0; r < NREAD; ++r) read_one(a_region + a0, b_region + b0, 0, 0, r);
             }
         }
-        uint8_t* stage = a_region + l2 + wave * (32 * FN * 64);
+        uint8_t* stage = (DEEP_B ? b_region + b2 : a_region + a2) + wave * (32 * FN * 64);
         if (SWIGLU)
             amax = store_h_fp8<FM, FN, WM>(acc, c_row0, c_rows, c_n0, static_cast<uint8_t*>(C), N, wm, wn, lane, stage,
                                            s0, s1, s2, amax);
@@ -408,6 +421,8 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
     }
 }
 
+static int g_fp8_deep_b = 1;   // three LDS stages for the weight tile (0: for the activation tile)
+
 template <bool SWIGLU>
 void launch_fp8(const void* A, const int32_t* offsets, int r_max, int E, int N, int K, const void* B0, const void* B1,
                 void* C, float s0, float s1, float s2, float* amax, hipStream_t s) {
@@ -416,12 +431,14 @@ void launch_fp8(const void* A, const int32_t* offsets, int r_max, int E, int N, 
     const int ntn = (N + OUTN - 1) / OUTN;
     // (the gate/up kernel has no registers to spare for the second loop: down projection only)
     const bool idle_skip = !SWIGLU && persist_idle_skip(E);
-    auto kern = idle_skip ? gemm_fp8_persist_kernel<SWIGLU, !SWIGLU> : gemm_fp8_persist_kernel<SWIGLU, false>;
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[idle_skip]) {
+    const bool deep = g_fp8_deep_b != 0;
+    auto kern = deep ? (idle_skip ? gemm_fp8_persist_kernel<SWIGLU, !SWIGLU, true> : gemm_fp8_persist_kernel<SWIGLU, false, true>)
+                     : (idle_skip ? gemm_fp8_persist_kernel<SWIGLU, !SWIGLU, false> : gemm_fp8_persist_kernel<SWIGLU, false, false>);
+    static bool attr_set[2][2] = {{false, false}, {false, false}};
+    if (!attr_set[deep][idle_skip]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)smem);
-        attr_set[idle_skip] = true;
+        attr_set[deep][idle_skip] = true;
     }
     const int grid = min(persist_grid(), grid_for(r_max, E, 256, ntn));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), smem, s, static_cast<const uint8_t*>(A), offsets, E, N, K,
@@ -429,6 +446,8 @@ void launch_fp8(const void* A, const int32_t* offsets, int r_max, int E, int N, 
 }
 
 }  // namespace
+
+void set_fp8_deep_b(int v) { g_fp8_deep_b = v; }
 
 bool fp8_ffn_supported(int H, int F) { return H % 128 == 0 && F % 128 == 0 && H >= 256 && F >= 256; }
 
