@@ -468,8 +468,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     };
     // one k-step in issue order: NSLOT slots of {MPS MFMAs on set mf_buf; up to
     // 2 fragment reads of k-step rd_s into the other set; one direct load}
+    // `aside`: scalar bookkeeping run under the MFMAs of slot 1 (the next period's load sources), so that it does
+    // not sit between two k-tiles with the matrix pipe empty
     auto kstep = [&](int mf_buf, const uint8_t* rd_a, const uint8_t* rd_b, int rd_s, int ld_begin, int ld_end,
-                     const Src& se, const Src& sl, uint8_t* ld_b, uint8_t* ld_a) {
+                     const Src& se, const Src& sl, uint8_t* ld_b, uint8_t* ld_a, auto&& aside) {
         int m = 0, rd = 0, ld = ld_begin;
 #pragma unroll
         for (int slot = 0; slot < NSLOT; ++slot) {
@@ -478,6 +480,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
                 mfma_one(mf_buf, m);
                 ++m;
             }
+            if (slot == 1) aside();
             // the k-step's first MFMA waits (lgkmcnt) for the fragments read during the previous k-step; keep
             // this k-step's reads behind it, or the compiler hoists them and that wait also covers reads issued
             // a moment ago (a full LDS round trip in front of every k-step)
@@ -541,17 +544,32 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         // matrix pipe and the LDS reads alone (under a power cap that is clock for the other workgroups).
         const bool wave_idle = IDLE_SKIP && wm * WM >= c_rows;   // wave-uniform
         if (!wave_idle) {
+        // sources of the loads of k-tiles kt+1 and kt+2.  With one wave per SIMD (four waves) nothing covers the
+        // scalar arithmetic that forms them if it sits between two k-tiles (some fifty instructions with the
+        // matrix pipe empty), so there they are carried from period to period: the pair a period needs is the
+        // previous period's second source and one computed under the MFMAs of the previous period's k-step 2 (a
+        // tile's first period forms its own: the next tile's third k-tile need not exist).  With two waves per
+        // SIMD the other wave covers it, and the carried form measured 1.7 % slower.
+        constexpr bool CARRY = NW == 4;
+        Src s1 = src(1), s2 = src(2), s3 = s2;
+        auto nothing = [] {};
         for (int kt = 0; kt < c_kt; ++kt) {
-            const Src s1 = src(kt + 1), s2 = src(kt + 2);
+            if constexpr (!CARRY) {
+                s1 = src(kt + 1);
+                s2 = src(kt + 2);
+            }
             const uint8_t* ca = a_region + a0;
             const uint8_t* cb = b_region + b0;
             // this period fills early(kt+1) and late(kt+2)
             uint8_t* lb = b_region + (DEEP_B ? b2 : b1);
             uint8_t* la = a_region + (DEEP_B ? a1 : a2);
             __builtin_amdgcn_sched_barrier(0);
-            kstep(0, ca, cb, 1, LA, LB, s1, s2, lb, la);  // k-step 0
-            kstep(1, ca, cb, 2, LB, LC, s1, s2, lb, la);  // k-step 1
-            kstep(0, ca, cb, 3, LC, LC, s1, s2, lb, la);  // k-step 2
+            kstep(0, ca, cb, 1, LA, LB, s1, s2, lb, la, nothing);  // k-step 0
+            kstep(1, ca, cb, 2, LB, LC, s1, s2, lb, la, nothing);  // k-step 1
+            if constexpr (CARRY)
+                kstep(0, ca, cb, 3, LC, LC, s1, s2, lb, la, [&] { s3 = src(kt + 3); });  // k-step 2
+            else
+                kstep(0, ca, cb, 3, LC, LC, s1, s2, lb, la, nothing);
             // early(kt+1) was issued before late(kt+2) in this period and late(kt+1) a period
             // ago: all but the PL youngest loads must have landed; this wave's
             // fragment reads of k-tile kt are in registers (lgkmcnt(0))
@@ -560,8 +578,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
             __builtin_amdgcn_sched_barrier(0);
             // k-step 3: first fragments of k-tile kt+1; the early operand's slot of k-tile
             // kt is free, the head of early(kt+2) goes into it
-            kstep(1, a_region + a1, b_region + b1, 0, 0, LA, s2, s2, b_region + b0, a_region + a0);
+            kstep(1, a_region + a1, b_region + b1, 0, 0, LA, s2, s2, b_region + b0, a_region + a0, nothing);
             rotate();
+            if constexpr (CARRY) {
+                s1 = s2;
+                s2 = s3;
+            }
         }
         } else {
             for (int kt = 0; kt < c_kt; ++kt) {

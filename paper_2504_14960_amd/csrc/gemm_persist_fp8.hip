@@ -297,12 +297,15 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
     };
     // one k-step in issue order: NSLOT slots of {one MFMA on set mf_buf; up to 2
     // fragment reads of k-step rd_s into the other set; one direct load}
+    // `aside`: scalar bookkeeping run under the MFMA of a late slot (the next period's load sources; see
+    // gemm_persist.hip: with one wave per SIMD nothing else covers it)
     auto kstep = [&](int mf_buf, const uint8_t* rd_a, const uint8_t* rd_b, int rd_s, int ld_begin, int ld_end,
-                     const Src& se, const Src& sl, uint8_t* ld_b, uint8_t* ld_a) {
+                     const Src& se, const Src& sl, uint8_t* ld_b, uint8_t* ld_a, auto&& aside) {
         int rd = 0, ld = ld_begin;
 #pragma unroll
         for (int slot = 0; slot < NSLOT; ++slot) {
             mfma_one(mf_buf, slot);
+            if (slot == NSLOT - 4) aside();
             // the first MFMA waits for the previous k-step's fragment reads only: keep the new reads behind it
             if (slot == 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -357,20 +360,25 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
         // only issues its share of the loads and meets the barriers (see gemm_persist.hip)
         const bool wave_idle = IDLE_SKIP && wm * WM >= c_rows;   // wave-uniform
         if (!wave_idle) {
+        // the load sources of k-tiles kt+1 and kt+2 are carried from period to period; the one a period adds is
+        // formed under the MFMAs of the previous period (a tile's first period forms its own)
+        Src q1 = src(1), q2 = src(2), q3 = q2;
+        auto nothing = [] {};
         for (int kt = 0; kt < KT; ++kt) {
-            const Src q1 = src(kt + 1), q2 = src(kt + 2);
             __builtin_amdgcn_sched_barrier(0);
             // k-step 0: rest of early(kt+1), all of late(kt+2)
             kstep(0, a_region + a0, b_region + b0, 1, LA, NLOAD, q1, q2, b_region + (DEEP_B ? b2 : b1),
-                  a_region + (DEEP_B ? a1 : a2));
+                  a_region + (DEEP_B ? a1 : a2), [&] { q3 = src(kt + 3); });
             // all but the PL youngest loads (those of late(kt+2)) have landed; this
             // wave's fragment reads of k-tile kt are in registers
             __builtin_amdgcn_s_waitcnt((PL & 0xF) | ((PL >> 4) << 14));
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             // k-step 1: first fragments of k-tile kt+1, head of early(kt+2) into the freed slot
-            kstep(1, a_region + a1, b_region + b1, 0, 0, LA, q2, q2, b_region + b0, a_region + a0);
+            kstep(1, a_region + a1, b_region + b1, 0, 0, LA, q2, q2, b_region + b0, a_region + a0, nothing);
             rotate();
+            q1 = q2;
+            q2 = q3;
         }
         } else {
             for (int kt = 0; kt < KT; ++kt) {
