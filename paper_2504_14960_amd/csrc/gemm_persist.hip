@@ -210,7 +210,7 @@ __device__ __forceinline__ void store_tile_staged(f32x16 (&acc)[FM][FN], int t_r
 // ahead) and two stages for the weight tile; true: the other way round -- the weights are what streams in from
 // HBM (every weight byte is used by one M-group only), the activation panels are re-read from the caches.
 template <int BM, int BN, int WGM, int WGN, int MODE, bool GROUPK = false, bool KMAJ = false, bool IDLE_SKIP = false,
-          bool DEEP_B = false>
+          bool DEEP_B = false, bool BY_ROUND = true>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const bf16_t* __restrict__ A, const int32_t* __restrict__ offsets, int E, int N, int K,
     const bf16_t* __restrict__ B0, const bf16_t* __restrict__ B1, bf16_t* __restrict__ C, bf16_t* __restrict__ GU,
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     // tiles are dealt to the XCDs round by round, except in the many-expert instantiations (measured: there the
     // gate/up GEMM loses 1 %, and the two GEMMs of a layer must walk the rows in the same order)
     typename std::conditional<KMAJ, WgradSchedKM<BM, BN>,
-                              typename std::conditional<GROUPK, WgradSched<BM, BN>, TileSched<BM, !IDLE_SKIP>>::type>::type sched;
+                              typename std::conditional<GROUPK, WgradSched<BM, BN>, TileSched<BM, BY_ROUND>>::type>::type sched;
     if constexpr (GROUPK)
         sched.init(offsets, E, ntn, N, lane);
     else
@@ -640,13 +640,17 @@ void launch_persist(const void* A, const int32_t* offsets, int r_max, int E, int
     const int ntn = (N + OUTN - 1) / OUTN;
     // many experts = many ragged tail tiles: the instantiation whose idle waves skip the multiplication
     const bool idle_skip = MODE != 3 && persist_idle_skip(E);
-    auto kern = idle_skip ? gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, (MODE != 3), DEEP_B>
-                          : gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, false, DEEP_B>;
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[idle_skip]) {
+    // few experts: whole rounds of tiles are dealt to the XCDs round by round; many: contiguous shares (measured)
+    const bool by_round = MODE == 3 || E < 16;
+    auto kern = idle_skip ? (by_round ? gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, (MODE != 3), DEEP_B, true>
+                                      : gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, (MODE != 3), DEEP_B, false>)
+                          : (by_round ? gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, false, DEEP_B, true>
+                                      : gemm_bf16_persist_kernel<BM, BN, WGM, WGN, MODE, false, false, false, DEEP_B, false>);
+    static bool attr_set[2][2] = {{false, false}, {false, false}};
+    if (!attr_set[idle_skip][by_round]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   (int)smem);
-        attr_set[idle_skip] = true;
+        attr_set[idle_skip][by_round] = true;
     }
     // never more workgroups than the static bound on the tile count
     const int grid = min(persist_grid(), grid_for(r_max, E, BM, ntn));
