@@ -69,6 +69,11 @@ def parse_args():
                     help="also time what ONE GPU of an S-rank expert-parallel group of this workload does between the "
                          "two All-to-All-Vs: gather the received chunks by expert, run its E/S experts, gather back "
                          "by source (every rank holding this workload's token count; no collective is run)")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the two expert GEMMs on UNIFORM experts (every expert the same whole number of "
+                         "256-row tiles, the workload's weights and token values) against the vendor library's GEMM "
+                         "(torch.matmul, one call per expert, no grouping, no SwiGLU) on the same operands: context "
+                         "for the roofline fraction, bf16 workloads only")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="moe_set_option knob for sweeps, e.g. gemm_variant=40 (repeatable)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -549,6 +554,54 @@ def main():
             "layer_useful_tflops_fwd_bwd": round(18.0 * R * H * F / ((fms + bms) * 1e-3) / 1e12, 1),
             "note": "weights_transpose re-lays the three expert weight tensors once per optimizer step; "
                     "with several micro-batches per step it is paid once, not per backward"}
+    if args.library_gemm and bf16 and not fp8:
+        s0 = sets[0]
+        rows_e = max(256, (R // E) // 256 * 256)          # whole tiles per expert, about the workload's row count
+        Ru = rows_e * E
+        offs_u = torch.arange(0, Ru + 1, rows_e, dtype=torch.int32, device="cuda")
+        xu = s0["x_perm"][:Ru] if Ru <= r_max else s0["x_perm"].repeat((Ru + r_max - 1) // r_max, 1)[:Ru]
+        hu = torch.empty((Ru, F), dtype=tdt, device="cuda")
+        yu = torch.empty((Ru, H), dtype=tdt, device="cuda")
+        gu_lib = torch.empty((rows_e, 2 * F), dtype=tdt, device="cuda")
+        y_lib = torch.empty((rows_e, H), dtype=tdt, device="cuda")
+        # the library multiplies by one [2F, H] matrix per expert (gate rows, then up rows): same FLOP, no activation
+        w_gu = [torch.cat([w["w_gate"][e], w["w_up"][e]]).t() for e in range(min(E, 8))]
+        w_dn = [w["w_down"][e].t() for e in range(min(E, 8))]
+
+        def lib_gate_up():
+            for e in range(E):
+                torch.matmul(xu[e * rows_e:(e + 1) * rows_e], w_gu[e % len(w_gu)], out=gu_lib)
+
+        def lib_down():
+            for e in range(E):
+                torch.matmul(hu[e * rows_e:(e + 1) * rows_e], w_dn[e % len(w_dn)], out=y_lib)
+
+        def timed_ms(fn, n=8, wu=3):
+            for _ in range(wu):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        res = {}
+        for nm, ours, theirs, flop in (
+                ("gate_up", lambda: moe.expert_gate_up(xu, offs_u, w["w_gate"], w["w_up"], hu), lib_gate_up, 4.0 * Ru * H * F),
+                ("down", lambda: moe.expert_down(hu, offs_u, w["w_down"], yu), lib_down, 2.0 * Ru * H * F)):
+            # interleaved, twice, so that both sides see the same clocks
+            t_o = [timed_ms(ours), 0.0]
+            t_l = [timed_ms(theirs), 0.0]
+            t_o[1], t_l[1] = timed_ms(ours), timed_ms(theirs)
+            res[nm] = {"this_tflops": [round(flop / (t * 1e-3) / 1e12, 1) for t in t_o],
+                       "library_tflops": [round(flop / (t * 1e-3) / 1e12, 1) for t in t_l]}
+        res["shape"] = {"experts": E, "rows_per_expert": rows_e, "H": H, "F": F}
+        res["note"] = ("uniform experts; library = torch.matmul (hipBLASLt), one call per expert on the same operands, "
+                       "gate and up weights as one [2F, H] matrix, no SwiGLU, its output overwritten by every call")
+        out["library_gemm"] = res
     if args.permute_variants and capacity > 0:
         s0 = sets[0]
         vws = torch.empty(moe.permute_variant_workspace_bytes(T, K, E) + 256, dtype=torch.uint8, device="cuda")

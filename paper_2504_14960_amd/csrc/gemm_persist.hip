@@ -319,7 +319,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
     const int frow = tid / CPR, fchunk = tid % CPR;
     const uint32_t k2 = (uint32_t)K * 2u;
     const uint32_t vrow = (uint32_t)frow * k2;
-    const uint32_t vswz = (uint32_t)((fchunk ^ (frow & 7)) * 16);
+    const uint32_t vswz = (uint32_t)((fchunk ^ lds_swizzle(frow)) * 16);   // every pass starts at a multiple of 16 rows
     const uint32_t step = (uint32_t)RPP * k2;
     const int wbase = (wave * 64 / CPR) * ROWB;
 
@@ -400,7 +400,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
 
     const int fr = lane & 31, fk = lane >> 5;
     int a_off[FM], b_off[FN];
-    const int f_sw = fr & 7;  // every fragment row is fr mod 8 (fragments start at multiples of 32)
+    const int f_sw = lds_swizzle(fr);  // fragments start at multiples of 32 rows
     if constexpr (KMAJ) {
         // lane (group g = lane / 16, s = lane % 16) addresses row 4 (g / 2) + s / 4 of an 8-row block, features
         // 16 (g % 2) + 4 (s % 4) .. + 3 of the fragment's 32; its row decides the swizzle of the 64-byte unit

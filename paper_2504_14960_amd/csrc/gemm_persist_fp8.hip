@@ -189,7 +189,7 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
     const int frow = tid / CPR, fchunk = tid % CPR;
     const uint32_t rowb = (uint32_t)K;
     const uint32_t vrow = (uint32_t)frow * rowb;
-    const uint32_t vswz = (uint32_t)((fchunk ^ (frow & 7)) * 16);
+    const uint32_t vswz = (uint32_t)((fchunk ^ lds_swizzle(frow)) * 16);
     const uint32_t step = (uint32_t)RPP * rowb;
     const int wbase = (wave * 64 / CPR) * ROWB;
     auto fetch_a = [&](int p, const uint8_t* base, uint32_t lim, uint8_t* st) {
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(256) void gemm_fp8_persist_kernel(
 
     const int fr = lane & 31, fk = lane >> 5;
     int a_off[FM], b_off[FN];
-    const int f_sw = fr & 7;
+    const int f_sw = lds_swizzle(fr);
 #pragma unroll
     for (int i = 0; i < FM; ++i) a_off[i] = (wm * WM + i * 32 + fr) * ROWB;
 #pragma unroll

@@ -122,14 +122,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     for (int p = 0; p < PA; ++p) {
         const int r = p * RPP + frow;
         const int rr = min(r, tile.rows - 1);  // ragged tail: re-read a valid row, result discarded
-        a_goff[p] = (uint32_t)rr * (uint32_t)K * 2u + (uint32_t)((fchunk ^ (r & 7)) * 16);
+        a_goff[p] = (uint32_t)rr * (uint32_t)K * 2u + (uint32_t)((fchunk ^ lds_swizzle(r)) * 16);
     }
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
         const int r = p * RPP + frow;
         int f = SWIGLU ? (r % (BN / 2)) : r;
         f = min(f, N - 1 - n0);
-        b_goff[p] = (uint32_t)f * (uint32_t)K * 2u + (uint32_t)((fchunk ^ (r & 7)) * 16);
+        b_goff[p] = (uint32_t)f * (uint32_t)K * 2u + (uint32_t)((fchunk ^ lds_swizzle(r)) * 16);
     }
     const int wbase = (wave * 64 / CPR) * ROWB;
 
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
     for (int i = 0; i < FM; ++i) {
         const int r = wm * WM + i * 32 + fr;
         a_off[i] = r * ROWB;
-        a_sw[i] = r & 7;
+        a_sw[i] = lds_swizzle(r);
     }
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_pipe3_kernel(
             r = wn * WN + j * 32 + fr;
         }
         b_off[j] = r * ROWB;
-        b_sw[j] = r & 7;
+        b_sw[j] = lds_swizzle(r);
     }
 
     f32x16 acc[FM][FN];

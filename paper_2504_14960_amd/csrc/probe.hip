@@ -43,12 +43,12 @@ __global__ __launch_bounds__(256) void probe_mfma_bf16_kernel(const uint32_t* __
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int r = row_a + 32 * i;
-                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lds + r * 128 + ((piece ^ (r & 7)) << 4)));
+                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lds + r * 128 + ((piece ^ lds_swizzle(r)) << 4)));
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int r = row_b + 32 * j;
-                b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lds + 32768 + r * 128 + ((piece ^ (r & 7)) << 4)));
+                b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lds + 32768 + r * 128 + ((piece ^ lds_swizzle(r)) << 4)));
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -96,8 +96,8 @@ __global__ __launch_bounds__(256) void probe_mfma_fp8_kernel(const uint32_t* __r
     const int row_a = (wave >> 1) * 128 + fr, row_b = (wave & 1) * 128 + fr;
     auto frag = [&](const uint8_t* base, int r, int ks) -> probe_i32x8 {
         const int piece = 4 * ks + 2 * fk;
-        const u32x4 lo = *reinterpret_cast<const u32x4*>(base + r * 128 + ((piece ^ (r & 7)) << 4));
-        const u32x4 hi = *reinterpret_cast<const u32x4*>(base + r * 128 + (((piece + 1) ^ (r & 7)) << 4));
+        const u32x4 lo = *reinterpret_cast<const u32x4*>(base + r * 128 + ((piece ^ lds_swizzle(r)) << 4));
+        const u32x4 hi = *reinterpret_cast<const u32x4*>(base + r * 128 + (((piece + 1) ^ lds_swizzle(r)) << 4));
         probe_i32x8 v;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
