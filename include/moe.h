@@ -524,7 +524,14 @@ moe_status_t moe_gemm_clock_sample(uint64_t* ticks);
 
 /* Tuning knobs for experiments (process-wide, not thread-safe; defaults are
  * the tuned ones).  Unknown names return MOE_ERR_INVALID_ARG.  Names:
- * "gemm_variant" (0 = auto); "gemm_workgroups" (workgroups launched by the
+ * "gemm_variant" (bf16 expert FFN: 0 = auto = 43 with the one-workgroup-per-tile
+ * kernel for layers whose H or F is below 128; 40 / 41 = persistent kernel with
+ * three LDS stages for the activation tile, 4 / 8 waves; 42 / 43 = three stages
+ * for the weight tile, 4 / 8 waves; 30 / 31 = one workgroup per tile, 4 / 8
+ * waves; 99 = the plain LDS-tiled kernel of the fp32 and odd-shape layers;
+ * any other value makes the expert calls return MOE_ERR_UNSUPPORTED);
+ * "fp8_deep_weights" (FP8 expert GEMMs: 1, the default = three LDS stages for
+ * the weight tile, 0 = for the activation tile); "gemm_workgroups" (workgroups launched by the
  * persistent grouped-GEMM kernels; 0 = one per compute unit, values below 8
  * are raised to 8); "router_tile" (16-token blocks per router workgroup: 1, 2
  * or 4; 0 = chosen from T and E); "wgrad_rowmajor" (1 = the expert FFN's backward
