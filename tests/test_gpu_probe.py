@@ -19,11 +19,11 @@ def test_probe_accumulates_the_products_of_its_operand_image():
     ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
     moe.probe_mfma_bf16(image, iters, nwg, sink, ticks)
     torch.cuda.synchronize()
-    # the image is read as the GEMM's LDS tiles are laid out: the 16-byte piece p of row r sits at piece p ^ (r & 7)
+    # the image is read as the GEMM's LDS tiles are laid out: the 16-byte piece p of row r sits at piece p ^ ((r >> 1) & 7)
     def logical(m):
         v = values(m).reshape(256, 8, 8)
         r = np.arange(256)[:, None]
-        return v[r, np.arange(8)[None, :] ^ (r & 7)].reshape(256, 64)
+        return v[r, np.arange(8)[None, :] ^ ((r >> 1) & 7)].reshape(256, 64)
     la, lb = logical(a), logical(b)
     # the four waves cover the 256 x 256 block of dot products once per iteration
     want = iters * float(la.sum(axis=0) @ lb.sum(axis=0))
@@ -56,10 +56,10 @@ def test_fp8_probe_accumulates_the_products_of_its_operand_image():
     moe.probe_mfma_fp8(to_dev(np.ascontiguousarray(codes.reshape(-1))), iters, nwg, sink, ticks)
     torch.cuda.synchronize()
 
-    def logical(m):     # 16-byte piece p of row r sits at piece p ^ (r & 7)
+    def logical(m):     # 16-byte piece p of row r sits at piece p ^ ((r >> 1) & 7)
         v = m.reshape(256, 8, 16)
         r = np.arange(256)[:, None]
-        return v[r, np.arange(8)[None, :] ^ (r & 7)].reshape(256, 128)
+        return v[r, np.arange(8)[None, :] ^ ((r >> 1) & 7)].reshape(256, 128)
     la, lb = logical(vals[0]).astype(np.float64), logical(vals[1]).astype(np.float64)
     want = iters * float(la.sum(axis=0) @ lb.sum(axis=0))
     got = sink.cpu().numpy().astype(np.float64).reshape(nwg, 256).sum(axis=1)
