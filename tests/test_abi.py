@@ -48,6 +48,19 @@ def test_max_rows_and_workspace_sizes():
     offs = list(lay.values())
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert moe.layer_workspace_bytes(256, 128, 8, 2, 256, 0, 0, moe.MOE_F32) >= offs[-1]
+    # moe_workspace_bytes is moe_layer_workspace_bytes for a layer without a shared expert
+    for T, H, E, K, F, cap, dt in ((256, 128, 8, 2, 256, 0, moe.MOE_F32), (8192, 6144, 8, 2, 16384, 0, moe.MOE_BF16),
+                                   (32768, 4096, 64, 6, 1408, 3072, moe.MOE_BF16)):
+        assert moe.workspace_bytes(T, H, E, K, F, cap, dt) == moe.layer_workspace_bytes(T, H, E, K, F, 0, cap, dt) > 0
+
+
+def test_clock_sample_pointer_is_checked_on_the_host():
+    import ctypes
+    L = moe.lib()
+    assert L.moe_gemm_clock_sample(ctypes.c_void_p(0)) == 0          # NULL switches the sampling off
+    assert L.moe_gemm_clock_sample(ctypes.c_void_p(12)) != 0         # not 8-byte aligned: refused, nothing stored
+    assert b"aligned" in L.moe_last_error()
+    assert L.moe_gemm_clock_sample(ctypes.c_void_p(0)) == 0
 
 
 def test_argument_errors_are_reported_on_the_host():

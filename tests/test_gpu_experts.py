@@ -143,3 +143,39 @@ def test_all_experts_empty_is_a_no_op():
     inp, x_perm, offsets, h_ref, y_ref = _case(H=128, F=128, E=4, counts=[0, 0, 0, 0], seed=4600, r_pad=16)
     h, y = _run(x_perm, offsets, inp, 0, r_max=16)
     assert (y == 0).all() and (h == 0).all()
+
+
+def test_clock_sample_reports_a_plausible_shader_clock_and_leaves_the_results_alone(ragged_case):
+    """moe_gemm_clock_sample: workgroup 0 of a persistent GEMM launch writes its shader-clock and 100 MHz ticks."""
+    import torch
+    import paper_2504_14960_amd as moe
+    inp, x_perm, offsets, h_ref, y_ref = ragged_case
+    E, F, H = inp["w_gate"].shape
+    dx, doff = to_dev(x_perm), to_dev(offsets)
+    wg, wu, wd = to_dev(inp["w_gate"]), to_dev(inp["w_up"]), to_dev(inp["w_down"])
+    h = torch.zeros((x_perm.shape[0], F), dtype=dx.dtype, device="cuda")
+    y = torch.zeros((x_perm.shape[0], H), dtype=dx.dtype, device="cuda")
+    ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
+    moe.gemm_clock_sample(ticks)
+    try:
+        moe.expert_gate_up(dx, doff, wg, wu, h)
+        torch.cuda.synchronize()
+        t_gu = ticks.cpu().tolist()
+        moe.expert_down(h, doff, wd, y)
+        torch.cuda.synchronize()
+        t_dn = ticks.cpu().tolist()
+    finally:
+        moe.gemm_clock_sample(None)
+    for tk in (t_gu, t_dn):
+        assert tk[0] > 0 and tk[1] > 0
+        mhz = 100.0 * tk[0] / tk[1]
+        assert 100.0 < mhz < 3000.0, mhz          # the part's clock range, generously
+    assert t_gu != t_dn                            # the second launch wrote its own sample
+    # sampling off again: the cells keep their last values, and the results are the oracle's either way
+    ticks.zero_()
+    moe.expert_gate_up(dx, doff, wg, wu, h)
+    moe.expert_down(h, doff, wd, y)
+    torch.cuda.synchronize()
+    assert ticks.cpu().tolist() == [0, 0]
+    assert_close(to_host(h), h_ref, True, "h after sampling")
+    assert_close(to_host(y), y_ref, True, "y_perm after sampling")
