@@ -178,11 +178,18 @@ def test_ffn_fp8_is_reproducible_and_handles_empty_input():
                                     None, torch.zeros((8, 192), dtype=torch.bfloat16, device="cuda"))
 
 
+# fused: the "permute_fused" option (0 = the maps from the three-kernel path, 1 = default dispatch, 2 / 3 = the maps from
+# the one-launch kernel with one / two tokens per wave); the quantising copy follows in either case.  Shapes with at
+# most 8 experts take the one-launch kernel: rows of 272 bytes up to 16 KiB, drops that leave whole tokens without a row
+@pytest.mark.parametrize("fused", [0, 1, 2, 3])
 @pytest.mark.parametrize("T,H,E,K,capacity", [(300, 256, 8, 2, 0), (1000, 136, 16, 4, 150), (257, 1032, 64, 8, 0),
-                                              (64, 64, 4, 1, 3)])
-def test_permute_fp8_writes_the_codes_of_the_permuted_rows(T, H, E, K, capacity):
+                                              (64, 64, 4, 1, 3), (700, 6144, 8, 2, 0), (513, 4096, 8, 2, 40),
+                                              (130, 8192, 8, 2, 0), (1000, 136, 8, 4, 150)])
+def test_permute_fp8_writes_the_codes_of_the_permuted_rows(T, H, E, K, capacity, fused):
     import torch
     import paper_2504_14960_amd as moe
+    if fused and E > 8:
+        pytest.skip("more than 8 experts: the dispatch is the three-kernel path whatever the option says")
     rng = np.random.default_rng(T + H)
     x = make_tokens(6000 + T, T, H, bf16=True)
     idx = np.stack([rng.permutation(E)[:K] for _ in range(T)]).astype(np.int32)
@@ -197,8 +204,12 @@ def test_permute_fp8_writes_the_codes_of_the_permuted_rows(T, H, E, K, capacity)
     roa, aor = torch.empty((T * K,), **i32), torch.empty((r_max,), **i32)
     ws = torch.empty((moe.permute_workspace_bytes(T, K, E) + 256,), dtype=torch.uint8, device="cuda")
     amax = torch.zeros(1, dtype=torch.float32, device="cuda")
-    moe.permute_fp8(to_dev(x), to_dev(idx), E, capacity, scale, xq[:r_max], counts, offsets, roa, aor, amax, ws)
-    torch.cuda.synchronize()
+    moe.set_option("permute_fused", fused)
+    try:
+        moe.permute_fp8(to_dev(x), to_dev(idx), E, capacity, scale, xq[:r_max], counts, offsets, roa, aor, amax, ws)
+        torch.cuda.synchronize()
+    finally:
+        moe.set_option("permute_fused", 1)
     np.testing.assert_array_equal(counts.cpu().numpy(), perm.counts)
     np.testing.assert_array_equal(offsets.cpu().numpy(), perm.offsets)
     np.testing.assert_array_equal(roa.cpu().numpy(), perm.row_of_assign)
