@@ -549,13 +549,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_persist_kernel(
         // matrix pipe empty), so there they are carried from period to period: the pair a period needs is the
         // previous period's second source and one computed under the MFMAs of the previous period's k-step 2 (a
         // tile's first period forms its own: the next tile's third k-tile need not exist).  With two waves per
-        // SIMD the other wave covers it, and the carried form measured 1.7 % slower.
+        // SIMD the other wave covers it, and the carried form measured 1.7 % slower; there only the first of the
+        // pair is carried and the second is formed at the top of the period.
         constexpr bool CARRY = NW == 4;
         Src s1 = src(1), s2 = src(2), s3 = s2;
         auto nothing = [] {};
         for (int kt = 0; kt < c_kt; ++kt) {
             if constexpr (!CARRY) {
-                s1 = src(kt + 1);
+                // the source of k-tile kt+1 is last period's second source; only the new one is formed here
+                if (kt > 0) s1 = s2;
                 s2 = src(kt + 2);
             }
             const uint8_t* ca = a_region + a0;
